@@ -1,0 +1,204 @@
+"""CPU oracle for the LoQT quantized low-rank linear layer (arxiv 2405.16528).
+
+THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only the tests, the smoke check
+and the cpu_baseline leg of the benchmark may import it.  It shares no code,
+table generator or helper with the HIP library; it never calls it.
+
+Everything is the plain definition, evaluated in numpy float64 in one pass:
+
+  codec  (paper sec. 5.1 "Neural Network Quantization and NF4"):
+      M_beta = max_{w in beta} |w_32|          blocks beta of 64 consecutive weights
+      code   = argmin_i | w / M_beta - q_i |   q_0..q_15 the NF4 levels
+      deq    = M_beta * q_code
+  layer  (paper sec. 2.2 "Equivalence of Gradient Updates", forward y = xW + xPB,
+          G^B = (xP)^T dL/dy = P^T G^W; sec. 2.4 "Quantized Training": W and P are
+          kept in NF4 and dequantised before the products; Alg. 1 line 5 scale s):
+      W_eff = deq(W_q) + s * deq(P_q) @ B      (out x in), PyTorch layout
+      y  = x @ W_eff^T ;  dx = dy @ W_eff ;  dB = s * deq(P_q)^T @ dy^T @ x
+  merge  (Alg. 1 line 5, sec. 2.4, sec. 2.5 first paragraph):
+      W_new = deq(W_q) + s * deq(P_q) @ B ;  (codes', absmax') = q_NF4(W_new)
+
+Layout convention used by every function here ("logical" form, no padding):
+  codes  : uint8 array (rows, cols), one code 0..15 per element
+  absmax : float32 array (rows, ceil(cols/64)); blocks run along a row and never
+           straddle rows; a short last block covers the elements present.
+pack_nf4 / unpack_nf4 convert to and from the byte layout of the C ABI.
+
+Readings of points the paper leaves open (each one is also listed in the design
+notes of the repository):
+  * orientation: PyTorch layout, W out x in, P out x r, B r x in, x T x in;
+  * s multiplies the low-rank term in forward, backward and merge alike;
+  * argmin is taken in exact real arithmetic, ties go to the lower index;
+  * an all-zero block stores absmax 0 and code 7 (the level 0.0);
+  * the quantiser's input is fp32 (M_beta is defined on 32-bit values), so the
+    merge rounds W_new to fp32 once (from the fp64 sum) before quantising;
+  * the 16 level values are not printed in the paper (it defers to QLoRA); the
+    table below is the published NF4 data type, typed in by hand, and pinned in
+    the tests against its construction from normal quantiles.
+Parity status: every function below is pinned by tests/test_oracle_*.py against
+closed forms, brute force in rational arithmetic, library routines and
+invariants; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+BLOCK = 64
+
+# The NF4 levels (QLoRA's "4-bit NormalFloat"), ascending; index = code.
+NF4_LEVELS = np.array(
+    [
+        -1.0,
+        -0.6961928009986877,
+        -0.5250730514526367,
+        -0.39491748809814453,
+        -0.28444138169288635,
+        -0.18477343022823334,
+        -0.09105003625154495,
+        0.0,
+        0.07958029955625534,
+        0.16093020141124725,
+        0.24611230194568634,
+        0.33791524171829224,
+        0.44070982933044434,
+        0.5626170039176941,
+        0.7229568362236023,
+        1.0,
+    ],
+    dtype=np.float64,
+)
+
+
+# ----------------------------------------------------------------------------
+# bf16 <-> float helpers (bf16 travels as raw uint16 bit patterns)
+# ----------------------------------------------------------------------------
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact value of bfloat16 bit patterns, as float64."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+def f32_to_bf16_rne(x: np.ndarray) -> np.ndarray:
+    """Round finite float32 to bfloat16 bit patterns, round-to-nearest-even."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    return ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+
+
+# ----------------------------------------------------------------------------
+# codec (sec. 5.1)
+# ----------------------------------------------------------------------------
+def nf4_quantize(w: np.ndarray):
+    """q_NF4 of a float32 matrix, blocks of 64 along each row (sec. 5.1).
+
+    Returns (codes uint8 (rows, cols), absmax float32 (rows, ceil(cols/64))).
+    code = #{ j in 0..14 : 2 w > (q_j + q_{j+1}) * M_beta }: this is the argmin of
+    |w/M_beta - q_i| in real arithmetic (w/M > midpoint  <=>  2w > (q_j+q_{j+1}) M
+    for M > 0) with ties resolved to the lower index.  q_j + q_{j+1} has at most 29
+    significant bits and M_beta 24, so the product is exact in float64 and no
+    rounding takes place anywhere in the decision.
+    """
+    w = np.asarray(w)
+    assert w.dtype == np.float32 and w.ndim == 2
+    rows, cols = w.shape
+    nblk = -(-cols // BLOCK)
+    wp = np.zeros((rows, nblk * BLOCK), dtype=np.float32)
+    wp[:, :cols] = w
+    wp = wp.reshape(rows, nblk, BLOCK)
+    absmax = np.max(np.abs(wp), axis=2)  # exact, float32
+    mid2 = NF4_LEVELS[:-1] + NF4_LEVELS[1:]  # 15 doubled midpoints, exact in fp64
+    w2 = 2.0 * wp.astype(np.float64)
+    m64 = absmax.astype(np.float64)
+    codes = np.zeros(wp.shape, dtype=np.uint8)
+    for j in range(15):
+        codes += w2 > (mid2[j] * m64)[:, :, None]
+    codes[absmax == 0.0] = 7  # all-zero block: level 0.0
+    codes = codes.reshape(rows, nblk * BLOCK)[:, :cols]
+    return np.ascontiguousarray(codes), absmax
+
+
+def nf4_dequantize_f64(codes: np.ndarray, absmax: np.ndarray) -> np.ndarray:
+    """M_beta * q_code as the exact real product (float64; 24 x 24 bits fit)."""
+    rows, cols = codes.shape
+    scale = np.repeat(absmax.astype(np.float64), BLOCK, axis=1)[:, :cols]
+    return NF4_LEVELS[codes] * scale
+
+
+def nf4_dequantize_f32(codes: np.ndarray, absmax: np.ndarray) -> np.ndarray:
+    """fp32 output of the stand-alone decoder: the exact product rounded once."""
+    return nf4_dequantize_f64(codes, absmax).astype(np.float32)
+
+
+def nf4_dequantize_bf16(codes: np.ndarray, absmax: np.ndarray) -> np.ndarray:
+    """bf16 output (bit patterns): the fp32 output rounded to nearest even."""
+    return f32_to_bf16_rne(nf4_dequantize_f32(codes, absmax))
+
+
+def pack_nf4(codes: np.ndarray, absmax: np.ndarray, ld: int):
+    """Logical form -> C-ABI byte layout with row pitch `ld` nibbles (ld % 64 == 0).
+
+    Row i starts at byte i*ld/2; element j sits in byte j//2, even j in the HIGH
+    nibble; positions cols..ld-1 hold code 7; absmax has ld/64 entries per row,
+    0.0 for blocks that lie entirely in the padding.
+    """
+    rows, cols = codes.shape
+    assert ld % BLOCK == 0 and ld >= cols
+    full = np.full((rows, ld), 7, dtype=np.uint8)
+    full[:, :cols] = codes
+    packed = (full[:, 0::2] << 4) | full[:, 1::2]
+    am = np.zeros((rows, ld // BLOCK), dtype=np.float32)
+    am[:, : absmax.shape[1]] = absmax
+    return np.ascontiguousarray(packed.astype(np.uint8)), am
+
+
+def unpack_nf4(packed: np.ndarray, absmax: np.ndarray, cols: int):
+    """C-ABI byte layout -> logical form (drops the padding)."""
+    rows = packed.shape[0]
+    full = np.empty((rows, packed.shape[1] * 2), dtype=np.uint8)
+    full[:, 0::2] = packed >> 4
+    full[:, 1::2] = packed & 0xF
+    nblk = -(-cols // BLOCK)
+    return np.ascontiguousarray(full[:, :cols]), np.ascontiguousarray(absmax[:, :nblk])
+
+
+# ----------------------------------------------------------------------------
+# layer (sec. 2.2, 2.4; Alg. 1)
+# ----------------------------------------------------------------------------
+def loqt_linear_fwd(x, Wq, Pq, B, s):
+    """y = x deq(W_q)^T + s (x B^T) deq(P_q)^T   in float64.
+
+    x: (T, in) bf16 bits; Wq = (codes, absmax) of (out, in); Pq of (out, r);
+    B: (r, in) bf16 bits.  Returns float64 (T, out).
+    """
+    xd = bf16_to_f64(x)
+    Bd = bf16_to_f64(B)
+    Wd = nf4_dequantize_f64(*Wq)
+    Pd = nf4_dequantize_f64(*Pq)
+    U = xd @ Bd.T
+    return xd @ Wd.T + s * (U @ Pd.T)
+
+
+def loqt_linear_bwd(dy, x, Wq, Pq, B, s):
+    """dx = dy deq(W_q) + s (dy deq(P_q)) B ;  dB = s deq(P_q)^T dy^T x   (float64).
+
+    The weight gradient goes to B alone (sec. 2.2: G^B = P^T G^W).
+    """
+    dyd = bf16_to_f64(dy)
+    xd = bf16_to_f64(x)
+    Bd = bf16_to_f64(B)
+    Wd = nf4_dequantize_f64(*Wq)
+    Pd = nf4_dequantize_f64(*Pq)
+    Z = dyd @ Pd
+    dx = dyd @ Wd + s * (Z @ Bd)
+    dB = s * (Z.T @ xd)
+    return dx, dB
+
+
+def loqt_merge_f64(Wq, Pq, B, s):
+    """The unquantised merged weight deq(W_q) + s deq(P_q) B in float64 (Alg. 1 l.5)."""
+    return nf4_dequantize_f64(*Wq) + s * (nf4_dequantize_f64(*Pq) @ bf16_to_f64(B))
+
+
+def loqt_merge_requant(Wq, Pq, B, s):
+    """W_q <- q_NF4( fp32( deq(W_q) + s deq(P_q) B ) ).  Returns (codes, absmax)."""
+    return nf4_quantize(loqt_merge_f64(Wq, Pq, B, s).astype(np.float32))
