@@ -1,0 +1,185 @@
+/*
+ * loqt.h -- C ABI of the MI355X (gfx950) LoQT hot-path library.
+ *
+ * LoQT ("Low-Rank Adapters for Quantized Pretraining", arxiv 2405.16528) trains a linear
+ * layer whose frozen weight W (out x in) and projection P (out x r) are stored in NF4 and
+ * whose only trainable tensor is the 16-bit factor B (r x in).  This library implements the
+ * three things every training run spends its time in:
+ *
+ *   forward   y  = x deq(W_q)^T + s (x B^T) deq(P_q)^T              (paper sec. 2.2, 2.4)
+ *   backward  dx = dy deq(W_q) + s (dy deq(P_q)) B
+ *             dB = s deq(P_q)^T dy^T x     (G^B = P^T G^W, sec. 2.2; no full dW is formed)
+ *   merge     W_q <- q_NF4( deq(W_q) + s deq(P_q) B )               (Alg. 1 line 5, sec. 2.4)
+ *
+ * plus the NF4 block codec itself (sec. 5.1).  Matrices use the PyTorch orientation
+ * (y = x W^T): W is out x in, P is out x r, B is r x in, x is T x in, y and dy are T x out.
+ *
+ * Conventions common to every call
+ *   - every data pointer is a DEVICE pointer (the descriptor structs themselves and the
+ *     descriptor array of the batched merge live in HOST memory);
+ *   - the caller owns every buffer; the library never allocates, frees or keeps a pointer;
+ *   - all matrices are row-major with an explicit row pitch ("ld", in elements);
+ *     a buffer of `rows` rows spans rows*ld elements;
+ *   - bf16 matrices: ld % 8 == 0 and a 16-byte aligned base (so that rows stay 16-byte
+ *     aligned); the logical column count is arbitrary;
+ *   - work is enqueued on the given hipStream_t (passed as void*; NULL = the null stream)
+ *     and the call returns without synchronising;
+ *   - arguments are checked on the host; on error a status is returned and NOTHING is
+ *     launched.  No exceptions, no hidden state, results are bit-deterministic;
+ *   - inputs must be finite.
+ *
+ * NF4 storage (sec. 5.1: blocks of 64 weights, one scale M_beta = max |w| per block)
+ *   codes  : rows x ld nibbles, two per byte.  Row i starts at byte i*ld/2; element j of
+ *            the row is in byte j/2, EVEN j in the HIGH nibble.  ld % 64 == 0, ld >= cols.
+ *            The nibble value is the index into the ascending 16-level NF4 table.
+ *   absmax : fp32, ld/64 per row; entry [i*(ld/64) + j/64] scales elements 64*(j/64)..+63 of
+ *            row i.  Blocks run along a row and never straddle rows; when cols % 64 != 0 the
+ *            last block of a row is short.  (rows = 1, cols = numel gives the flat blocking.)
+ *   Writers in this library fill nibbles cols..ld-1 with code 7 (the level 0.0) and give
+ *   blocks that lie wholly in that padding absmax 0.  Readers never depend on it.
+ *   An all-zero block is stored as absmax 0 / code 7.
+ */
+#ifndef LOQT_H
+#define LOQT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int loqt_status;
+enum {
+    LOQT_OK = 0,
+    LOQT_INVALID_ARG = 1,         /* NULL pointer, negative size, unknown enum value */
+    LOQT_BAD_SHAPE = 2,           /* pitch rule violated, operand shapes inconsistent, size 0 */
+    LOQT_MISALIGNED = 3,          /* base pointer alignment rule violated */
+    LOQT_WORKSPACE_TOO_SMALL = 4, /* ws_bytes < loqt_workspace_bytes(...) */
+    LOQT_LAUNCH_FAILED = 5        /* HIP reported an error at launch */
+};
+
+typedef uint16_t loqt_bf16; /* raw bfloat16 bits */
+
+/* A read-only NF4 matrix (device pointers, see "NF4 storage" above). */
+typedef struct loqt_nf4_mat {
+    const uint8_t *codes;
+    const float *absmax;
+    int64_t rows, cols; /* logical shape */
+    int64_t ld;         /* row pitch in nibbles, multiple of 64 */
+} loqt_nf4_mat;
+
+enum { LOQT_F32 = 0, LOQT_BF16 = 1 };                 /* output dtypes */
+enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2 };
+
+/* Human-readable name of a status code (static string). */
+const char *loqt_status_string(loqt_status st);
+
+/*
+ * nf4_quantize -- q_NF4 of sec. 5.1.
+ *   w      : fp32, rows x cols, pitch ld_w (elements; ld_w % 4 == 0, 16-byte aligned base)
+ *   codes  : out, rows * ld_q / 2 bytes;  absmax: out, rows * ld_q / 64 floats
+ * For every block beta of 64 consecutive elements of a row: M = max |w| (exact), and for
+ * each element the code is argmin_i |w/M - q_i| evaluated in exact arithmetic (ties to the
+ * lower index).  An all-zero block gives M = 0 and code 7.  Padding as described above.
+ */
+loqt_status nf4_quantize(const float *w, int64_t rows, int64_t cols, int64_t ld_w,
+                         uint8_t *codes, float *absmax, int64_t ld_q, void *hip_stream);
+
+/*
+ * nf4_dequantize -- q_NF4^{-1} of sec. 5.1: out[i][j] = M_beta * q[code].
+ *   out_dtype LOQT_F32 : one IEEE fp32 multiply (round to nearest even), ld_out % 4 == 0
+ *   out_dtype LOQT_BF16: that fp32 value rounded to nearest even bf16,    ld_out % 8 == 0
+ * Only columns 0..cols-1 of each output row are written.
+ */
+loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t rows, int64_t cols,
+                           int64_t ld_q, void *out, int out_dtype, int64_t ld_out,
+                           void *hip_stream);
+
+/*
+ * Bytes of device workspace the given operation needs for these sizes (0 is possible).
+ * The workspace must be 256-byte aligned; its contents are scratch.  Two calls that share a
+ * workspace must be ordered on the same stream.
+ *   FWD  : U = s x B^T                       (T x r bf16)
+ *   BWD  : Z = s dy deq(P_q) (T x r bf16) and the split-K partial sums of dB (fp32)
+ *   MERGE: none
+ */
+size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r);
+
+/*
+ * loqt_linear_fwd -- forward pass of the layer (sec. 2.2 "y = xW + xPB", with W and P
+ * dequantised from NF4 on the fly, sec. 2.4; s is the scale of Alg. 1 line 5).
+ *   y[T x out] = x[T x in] deq(Wq)^T + s * (x B^T) deq(Pq)^T
+ *   Wq: out x in, Pq: out x r, B: r x in (pitch ld_B), x pitch ld_x, y pitch ld_y.
+ * Products take bf16 operands (dequantised values rounded to nearest even) and accumulate in
+ * fp32; y is rounded to bf16 once.  The intermediate s*x*B^T is kept in bf16 in `ws`.
+ */
+loqt_status loqt_linear_fwd(const loqt_bf16 *x, int64_t ld_x, int64_t T,
+                            const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq,
+                            const loqt_bf16 *B, int64_t ld_B, float s,
+                            loqt_bf16 *y, int64_t ld_y,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * loqt_linear_bwd -- backward pass (sec. 2.2: the only weight gradient is G^B = P^T G^W).
+ *   Z  = s * dy deq(Pq)                          (T x r, kept in bf16 in `ws`, used twice)
+ *   dx = dy deq(Wq) + Z B                        (T x in, bf16; pass dx = NULL to skip it)
+ *   dB = Z^T x                                   (r x in; dB_dtype LOQT_F32 or LOQT_BF16)
+ *   accumulate != 0: dB_out = dB_in + dB (gradient accumulation), else dB_out = dB.
+ * The full out x in gradient of W is never formed.  dB is summed in fp32 in a fixed order.
+ */
+loqt_status loqt_linear_bwd(const loqt_bf16 *dy, int64_t ld_dy, const loqt_bf16 *x, int64_t ld_x,
+                            int64_t T, const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq,
+                            const loqt_bf16 *B, int64_t ld_B, float s,
+                            loqt_bf16 *dx, int64_t ld_dx,
+                            void *dB, int dB_dtype, int64_t ld_dB, int accumulate,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * loqt_merge_requant -- the periodic merge (Alg. 1 line 5; sec. 2.4: dequantise W_q and P_q,
+ * add P B, quantise again, one layer at a time).
+ *   W_new = deq(Wq) + s * deq(Pq) B   (fp32: fl32(M*q) + fp32-accumulated bf16 product)
+ *   (codes_out, absmax_out) = nf4_quantize(W_new), same pitch Wq->ld.
+ * codes_out / absmax_out may alias Wq->codes / Wq->absmax (in-place merge); they must not
+ * partially overlap them.  B is not modified (re-initialising it is the caller's business).
+ */
+loqt_status loqt_merge_requant(const loqt_nf4_mat *Wq, uint8_t *codes_out, float *absmax_out,
+                               const loqt_nf4_mat *Pq, const loqt_bf16 *B, int64_t ld_B, float s,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One layer of a batched merge (host struct; pointers inside are device pointers). */
+typedef struct loqt_merge_desc {
+    loqt_nf4_mat Wq;
+    uint8_t *codes_out;
+    float *absmax_out;
+    loqt_nf4_mat Pq;
+    const loqt_bf16 *B;
+    int64_t ld_B;
+    float s;
+} loqt_merge_desc;
+
+/*
+ * loqt_merge_requant_batched -- loqt_merge_requant over n_layers layers (descs: HOST array),
+ * enqueued back to back on one stream; layers are independent.  Every descriptor is checked
+ * before the first launch.
+ */
+loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *descs,
+                                       void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Optional per-kernel timing (diagnostics for benchmarks; off by default).
+ * While enabled, every kernel launch of the library is bracketed by HIP events recorded on
+ * the launch stream.  loqt_timing_read synchronises with the recorded events and returns,
+ * for kernel slot `slot` (0 <= slot < loqt_timing_slots()), its name, launch count and summed
+ * device time in milliseconds since the last loqt_timing_enable(1).  Not thread-safe; at most
+ * LOQT_TIMING_MAX_EVENTS launches are recorded per enable, later ones are not timed.
+ */
+#define LOQT_TIMING_MAX_EVENTS 65536
+void loqt_timing_enable(int on);
+int loqt_timing_slots(void);
+loqt_status loqt_timing_read(int slot, const char **name, int64_t *launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOQT_H */

@@ -1,0 +1,186 @@
+"""ctypes binding of libloqt.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for device
+memory and streams, nothing else), passes their pointers and pitches to the C ABI declared
+in include/loqt.h and raises LoqtError on a non-zero status.  There is no CPU fallback: if
+the library has not been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libloqt.so")
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it with `python -m paper_2405_16528_amd.build` "
+        "(there is no fallback path)")
+lib = C.CDLL(_LIB_PATH)
+
+F32, BF16 = 0, 1
+OP_FWD, OP_BWD, OP_MERGE = 0, 1, 2
+STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
+                4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
+
+
+class LoqtError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)}")
+
+
+class NF4MatC(C.Structure):
+    _fields_ = [("codes", C.c_void_p), ("absmax", C.c_void_p), ("rows", C.c_int64),
+                ("cols", C.c_int64), ("ld", C.c_int64)]
+
+
+class MergeDescC(C.Structure):
+    _fields_ = [("Wq", NF4MatC), ("codes_out", C.c_void_p), ("absmax_out", C.c_void_p),
+                ("Pq", NF4MatC), ("B", C.c_void_p), ("ld_B", C.c_int64), ("s", C.c_float)]
+
+
+_i64, _vp, _f, _i, _sz = C.c_int64, C.c_void_p, C.c_float, C.c_int, C.c_size_t
+_P = C.POINTER
+lib.loqt_status_string.restype = C.c_char_p
+lib.loqt_status_string.argtypes = [_i]
+lib.nf4_quantize.restype = _i
+lib.nf4_quantize.argtypes = [_vp, _i64, _i64, _i64, _vp, _vp, _i64, _vp]
+lib.nf4_dequantize.restype = _i
+lib.nf4_dequantize.argtypes = [_vp, _vp, _i64, _i64, _i64, _vp, _i, _i64, _vp]
+lib.loqt_workspace_bytes.restype = _sz
+lib.loqt_workspace_bytes.argtypes = [_i, _i64, _i64, _i64, _i64]
+lib.loqt_linear_fwd.restype = _i
+lib.loqt_linear_fwd.argtypes = [_vp, _i64, _i64, _P(NF4MatC), _P(NF4MatC), _vp, _i64, _f, _vp, _i64,
+                                _vp, _sz, _vp]
+lib.loqt_linear_bwd.restype = _i
+lib.loqt_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _i64, _P(NF4MatC), _P(NF4MatC), _vp, _i64, _f,
+                                _vp, _i64, _vp, _i, _i64, _i, _vp, _sz, _vp]
+lib.loqt_merge_requant.restype = _i
+lib.loqt_merge_requant.argtypes = [_P(NF4MatC), _vp, _vp, _P(NF4MatC), _vp, _i64, _f, _vp, _sz, _vp]
+lib.loqt_merge_requant_batched.restype = _i
+lib.loqt_merge_requant_batched.argtypes = [_i, _P(MergeDescC), _vp, _sz, _vp]
+lib.loqt_timing_enable.restype = None
+lib.loqt_timing_enable.argtypes = [_i]
+lib.loqt_timing_slots.restype = _i
+lib.loqt_timing_slots.argtypes = []
+lib.loqt_timing_read.restype = _i
+lib.loqt_timing_read.argtypes = [_i, _P(C.c_char_p), _P(_i64), _P(C.c_double)]
+
+
+def _check(st: int, where: str) -> None:
+    if st != 0:
+        raise LoqtError(st, where)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _pitch(t: torch.Tensor) -> int:
+    assert t.dim() == 2 and t.stride(1) == 1 and t.is_cuda
+    return t.stride(0)
+
+
+@dataclass
+class NF4Tensor:
+    """NF4 matrix on the device in the layout of include/loqt.h."""
+    codes: torch.Tensor   # uint8 (rows, ld/2)
+    absmax: torch.Tensor  # float32 (rows, ld/64)
+    rows: int
+    cols: int
+    ld: int
+
+    def c(self) -> NF4MatC:
+        return NF4MatC(self.codes.data_ptr(), self.absmax.data_ptr(), self.rows, self.cols, self.ld)
+
+    @staticmethod
+    def empty(rows: int, cols: int, ld: Optional[int] = None, device="cuda") -> "NF4Tensor":
+        ld = ld or (cols + 63) // 64 * 64
+        return NF4Tensor(torch.empty((rows, ld // 2), dtype=torch.uint8, device=device),
+                         torch.empty((rows, ld // 64), dtype=torch.float32, device=device), rows, cols, ld)
+
+
+def nf4_quantize(w: torch.Tensor, out: Optional[NF4Tensor] = None, cols: Optional[int] = None) -> NF4Tensor:
+    """w: float32 (rows, >=cols) on the GPU."""
+    rows = w.shape[0]
+    cols = cols if cols is not None else w.shape[1]
+    out = out or NF4Tensor.empty(rows, cols, device=w.device)
+    _check(lib.nf4_quantize(w.data_ptr(), rows, cols, _pitch(w), out.codes.data_ptr(), out.absmax.data_ptr(),
+                            out.ld, _stream()), "nf4_quantize")
+    return out
+
+
+def nf4_dequantize(q: NF4Tensor, out: torch.Tensor) -> torch.Tensor:
+    """out: float32 or bfloat16 (rows, >=cols) on the GPU; columns 0..cols-1 are written."""
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[out.dtype]
+    _check(lib.nf4_dequantize(q.codes.data_ptr(), q.absmax.data_ptr(), q.rows, q.cols, q.ld, out.data_ptr(), dt,
+                              _pitch(out), _stream()), "nf4_dequantize")
+    return out
+
+
+def loqt_workspace_bytes(op: int, T: int, out: int, inp: int, r: int) -> int:
+    return int(lib.loqt_workspace_bytes(op, T, out, inp, r))
+
+
+def loqt_linear_fwd(x, Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, y, ws) -> torch.Tensor:
+    T = x.shape[0]
+    _check(lib.loqt_linear_fwd(x.data_ptr(), _pitch(x), T, C.byref(Wq.c()), C.byref(Pq.c()), B.data_ptr(),
+                               _pitch(B), s, y.data_ptr(), _pitch(y), _ptr(ws), ws.numel() * ws.element_size(),
+                               _stream()), "loqt_linear_fwd")
+    return y
+
+
+def loqt_linear_bwd(dy, x, Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, dx, dB, accumulate: bool, ws):
+    T = x.shape[0]
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[dB.dtype]
+    _check(lib.loqt_linear_bwd(dy.data_ptr(), _pitch(dy), x.data_ptr(), _pitch(x), T, C.byref(Wq.c()),
+                               C.byref(Pq.c()), B.data_ptr(), _pitch(B), s, _ptr(dx),
+                               _pitch(dx) if dx is not None else 0, dB.data_ptr(), dt, _pitch(dB),
+                               1 if accumulate else 0, _ptr(ws), ws.numel() * ws.element_size(), _stream()),
+           "loqt_linear_bwd")
+    return dx, dB
+
+
+def loqt_merge_requant(Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, out: Optional[NF4Tensor] = None) -> NF4Tensor:
+    """out=None merges in place."""
+    out = out or Wq
+    _check(lib.loqt_merge_requant(C.byref(Wq.c()), out.codes.data_ptr(), out.absmax.data_ptr(), C.byref(Pq.c()),
+                                  B.data_ptr(), _pitch(B), s, None, 0, _stream()), "loqt_merge_requant")
+    return out
+
+
+def make_merge_descs(layers):
+    """layers: iterable of (Wq, out_or_None, Pq, B, s) -> ctypes array for the batched merge."""
+    layers = list(layers)
+    arr = (MergeDescC * len(layers))()
+    for d, (Wq, out, Pq, B, s) in zip(arr, layers):
+        out = out or Wq
+        d.Wq, d.codes_out, d.absmax_out = Wq.c(), out.codes.data_ptr(), out.absmax.data_ptr()
+        d.Pq, d.B, d.ld_B, d.s = Pq.c(), B.data_ptr(), _pitch(B), s
+    return arr
+
+
+def loqt_merge_requant_batched(descs) -> None:
+    _check(lib.loqt_merge_requant_batched(len(descs), descs, None, 0, _stream()), "loqt_merge_requant_batched")
+
+
+def timing_enable(on: bool) -> None:
+    lib.loqt_timing_enable(1 if on else 0)
+
+
+def timing_read() -> dict:
+    """{kernel name: (launches, total ms)} since the last timing_enable(True)."""
+    out = {}
+    for slot in range(lib.loqt_timing_slots()):
+        name, n, ms = C.c_char_p(), _i64(), C.c_double()
+        _check(lib.loqt_timing_read(slot, C.byref(name), C.byref(n), C.byref(ms)), "loqt_timing_read")
+        out[name.value.decode()] = (n.value, ms.value)
+    return out

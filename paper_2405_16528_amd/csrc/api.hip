@@ -1,0 +1,361 @@
+// C ABI of libloqt: argument checking, workspace layout, launch sequences, timing.
+#include <string.h>
+
+#include "loqt_internal.h"
+
+namespace loqt {
+
+// ---------------------------------------------------------------------------------------
+// per-kernel timing (diagnostics): events recorded around every launch while enabled
+// ---------------------------------------------------------------------------------------
+namespace {
+struct TimingState {
+    bool on = false;
+    int n = 0;
+    hipEvent_t* begin = nullptr;
+    hipEvent_t* end = nullptr;
+    int* slot = nullptr;
+    int created = 0;
+} g_timing;
+const char* kSlotNames[SLOT_COUNT] = {"nf4_quantize", "nf4_dequantize", "gemm_u",   "gemm_y",      "gemm_z",
+                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant"};
+}  // namespace
+
+TimedLaunch::TimedLaunch(int slot_, hipStream_t s) : stream(s), slot(slot_), idx(-1) {
+    if (!g_timing.on || g_timing.n >= LOQT_TIMING_MAX_EVENTS) return;
+    idx = g_timing.n++;
+    if (idx >= g_timing.created) {
+        (void)hipEventCreate(&g_timing.begin[idx]);
+        (void)hipEventCreate(&g_timing.end[idx]);
+        g_timing.created = idx + 1;
+    }
+    g_timing.slot[idx] = slot;
+    (void)hipEventRecord(g_timing.begin[idx], stream);
+}
+TimedLaunch::~TimedLaunch() {
+    if (idx >= 0) (void)hipEventRecord(g_timing.end[idx], stream);
+}
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+constexpr int64_t kMaxDim = (int64_t)1 << 30;  // index arithmetic inside the kernels is 32-bit per axis
+
+loqt_status check_nf4(const loqt_nf4_mat* m) {
+    if (!m || !m->codes || !m->absmax) return LOQT_INVALID_ARG;
+    if (m->rows < 0 || m->cols < 0 || m->ld < 0) return LOQT_INVALID_ARG;
+    if (m->rows == 0 || m->cols == 0 || m->rows > kMaxDim || m->cols > kMaxDim) return LOQT_BAD_SHAPE;
+    if (m->ld % 64 != 0 || m->ld < m->cols) return LOQT_BAD_SHAPE;
+    if (!aligned(m->codes, 16) || !aligned(m->absmax, 4)) return LOQT_MISALIGNED;
+    return LOQT_OK;
+}
+
+loqt_status check_bf16(const void* p, int64_t rows, int64_t cols, int64_t ld) {
+    if (!p) return LOQT_INVALID_ARG;
+    if (rows < 0 || cols < 0 || ld < 0) return LOQT_INVALID_ARG;
+    if (rows == 0 || cols == 0 || rows > kMaxDim || cols > kMaxDim) return LOQT_BAD_SHAPE;
+    if (ld % 8 != 0 || ld < cols) return LOQT_BAD_SHAPE;
+    if (!aligned(p, 16)) return LOQT_MISALIGNED;
+    return LOQT_OK;
+}
+
+#define LOQT_TRY(expr)                     \
+    do {                                   \
+        loqt_status st__ = (expr);         \
+        if (st__ != LOQT_OK) return st__;  \
+    } while (0)
+#define LOQT_HIP(expr)                                    \
+    do {                                                  \
+        if ((expr) != hipSuccess) return LOQT_LAUNCH_FAILED; \
+    } while (0)
+
+// shapes of the layer: W out x in, P out x r
+loqt_status check_layer(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const void* B, int64_t ld_B) {
+    LOQT_TRY(check_nf4(Wq));
+    LOQT_TRY(check_nf4(Pq));
+    if (Pq->rows != Wq->rows) return LOQT_BAD_SHAPE;
+    LOQT_TRY(check_bf16(B, Pq->cols, Wq->cols, ld_B));
+    return LOQT_OK;
+}
+
+size_t bwd_z_bytes(int64_t T, int64_t r) { return round_up((size_t)T * (size_t)round_up(r, 8) * 2, 256); }
+
+Operand nf4_operand(const loqt_nf4_mat* m, int rows, int K) {
+    Operand o;
+    o.ptr = m->codes;
+    o.absmax = m->absmax;
+    o.ld = m->ld;
+    o.rows = rows;
+    o.K = K;
+    return o;
+}
+Operand bf16_operand(const void* p, int64_t ld, int rows, int K) {
+    Operand o;
+    o.ptr = p;
+    o.absmax = nullptr;
+    o.ld = ld;
+    o.rows = rows;
+    o.K = K;
+    return o;
+}
+Operand no_operand() {
+    Operand o;
+    memset(&o, 0, sizeof(o));
+    return o;
+}
+
+loqt_status merge_checked(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                          const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
+                          hipStream_t st) {
+    const int out = (int)Wq->rows, in = (int)Wq->cols, r = (int)Pq->cols;
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    // transposed product: rows of the tile run along `in`
+    p.A[0] = bf16_operand(B, ld_B, in, r);  // B is r x in: K x rows
+    p.B[0] = nf4_operand(Pq, out, r);       // P is out x r: rows x K
+    p.A[1] = no_operand();
+    p.B[1] = no_operand();
+    p.M = in;
+    p.N = out;
+    p.alpha = s;
+    p.w_codes = Wq->codes;
+    p.w_absmax = Wq->absmax;
+    p.out_codes = codes_out;
+    p.out_absmax = absmax_out;
+    p.w_ld = Wq->ld;
+    p.w_cols = in;
+    // the tile grid must reach the padding columns cols..ld-1 as well
+    p.M = (int)Wq->ld;
+    p.A[0].rows = in;
+    LOQT_HIP(launch_gemm(GEMM_MERGE, p, st));
+    return LOQT_OK;
+}
+
+loqt_status check_merge(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                        const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B) {
+    if (!codes_out || !absmax_out) return LOQT_INVALID_ARG;
+    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
+    if (!aligned(codes_out, 16) || !aligned(absmax_out, 4)) return LOQT_MISALIGNED;
+    // full aliasing is allowed, partial overlap is not
+    const size_t cb = (size_t)Wq->rows * (size_t)(Wq->ld / 2), ab = (size_t)Wq->rows * (size_t)(Wq->ld / 64) * 4;
+    const uint8_t* ci = Wq->codes;
+    const uint8_t* ai = reinterpret_cast<const uint8_t*>(Wq->absmax);
+    const uint8_t* ao = reinterpret_cast<const uint8_t*>(absmax_out);
+    if (codes_out != ci && codes_out < ci + cb && ci < codes_out + cb) return LOQT_INVALID_ARG;
+    if (ao != ai && ao < ai + ab && ai < ao + ab) return LOQT_INVALID_ARG;
+    return LOQT_OK;
+}
+
+}  // namespace
+}  // namespace loqt
+
+using namespace loqt;
+
+extern "C" {
+
+const char* loqt_status_string(loqt_status st) {
+    switch (st) {
+        case LOQT_OK: return "LOQT_OK";
+        case LOQT_INVALID_ARG: return "LOQT_INVALID_ARG";
+        case LOQT_BAD_SHAPE: return "LOQT_BAD_SHAPE";
+        case LOQT_MISALIGNED: return "LOQT_MISALIGNED";
+        case LOQT_WORKSPACE_TOO_SMALL: return "LOQT_WORKSPACE_TOO_SMALL";
+        case LOQT_LAUNCH_FAILED: return "LOQT_LAUNCH_FAILED";
+    }
+    return "LOQT_UNKNOWN_STATUS";
+}
+
+loqt_status nf4_quantize(const float* w, int64_t rows, int64_t cols, int64_t ld_w, uint8_t* codes,
+                         float* absmax, int64_t ld_q, void* hip_stream) {
+    if (!w || !codes || !absmax) return LOQT_INVALID_ARG;
+    if (rows < 0 || cols < 0 || ld_w < 0 || ld_q < 0) return LOQT_INVALID_ARG;
+    if (rows == 0 || cols == 0 || rows > kMaxDim || cols > kMaxDim) return LOQT_BAD_SHAPE;
+    if (ld_w % 4 != 0 || ld_w < cols || ld_q % 64 != 0 || ld_q < cols) return LOQT_BAD_SHAPE;
+    if (!aligned(w, 16) || !aligned(codes, 16) || !aligned(absmax, 4)) return LOQT_MISALIGNED;
+    LOQT_HIP(launch_quantize(w, rows, cols, ld_w, codes, absmax, ld_q, (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+loqt_status nf4_dequantize(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
+                           int64_t ld_q, void* out, int out_dtype, int64_t ld_out, void* hip_stream) {
+    if (!codes || !absmax || !out) return LOQT_INVALID_ARG;
+    if (out_dtype != LOQT_F32 && out_dtype != LOQT_BF16) return LOQT_INVALID_ARG;
+    if (rows < 0 || cols < 0 || ld_q < 0 || ld_out < 0) return LOQT_INVALID_ARG;
+    if (rows == 0 || cols == 0 || rows > kMaxDim || cols > kMaxDim) return LOQT_BAD_SHAPE;
+    if (ld_q % 64 != 0 || ld_q < cols || ld_out < cols) return LOQT_BAD_SHAPE;
+    if (ld_out % (out_dtype == LOQT_BF16 ? 8 : 4) != 0) return LOQT_BAD_SHAPE;
+    if (!aligned(codes, 16) || !aligned(absmax, 4) || !aligned(out, 16)) return LOQT_MISALIGNED;
+    LOQT_HIP(launch_dequantize(codes, absmax, rows, cols, ld_q, out, out_dtype, ld_out,
+                               (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r) {
+    (void)out;
+    if (T <= 0 || in <= 0 || r <= 0) return 0;
+    switch (op) {
+        case LOQT_OP_FWD: return bwd_z_bytes(T, r);
+        case LOQT_OP_BWD:
+            return bwd_z_bytes(T, r) + round_up((size_t)gemm_db_splits(T, r, in) * (size_t)r * (size_t)in * 4, 256);
+        default: return 0;
+    }
+}
+
+loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_nf4_mat* Wq,
+                            const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
+                            loqt_bf16* y, int64_t ld_y, void* ws, size_t ws_bytes, void* hip_stream) {
+    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
+    const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
+    LOQT_TRY(check_bf16(x, T, in, ld_x));
+    LOQT_TRY(check_bf16(y, T, out, ld_y));
+    if (!ws) return LOQT_INVALID_ARG;
+    if (!aligned(ws, 256)) return LOQT_MISALIGNED;
+    if (ws_bytes < loqt_workspace_bytes(LOQT_OP_FWD, T, out, in, r)) return LOQT_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t ld_u = (int64_t)round_up(r, 8);
+    loqt_bf16* U = reinterpret_cast<loqt_bf16*>(ws);
+
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    // U = s x B^T
+    p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+    p.B[0] = bf16_operand(B, ld_B, (int)r, (int)in);
+    p.M = (int)T;
+    p.N = (int)r;
+    p.alpha = s;
+    p.C = U;
+    p.ldc = ld_u;
+    LOQT_HIP(launch_gemm(GEMM_U, p, st));
+    // y = x deq(W)^T + U deq(P)^T
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+    p.B[0] = nf4_operand(Wq, (int)out, (int)in);
+    p.A[1] = bf16_operand(U, ld_u, (int)T, (int)r);
+    p.B[1] = nf4_operand(Pq, (int)out, (int)r);
+    p.M = (int)T;
+    p.N = (int)out;
+    p.alpha = 1.0f;
+    p.C = y;
+    p.ldc = ld_y;
+    LOQT_HIP(launch_gemm(GEMM_Y, p, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
+                            const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B,
+                            float s, loqt_bf16* dx, int64_t ld_dx, void* dB, int dB_dtype, int64_t ld_dB,
+                            int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
+    const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
+    LOQT_TRY(check_bf16(dy, T, out, ld_dy));
+    LOQT_TRY(check_bf16(x, T, in, ld_x));
+    if (dx) LOQT_TRY(check_bf16(dx, T, in, ld_dx));
+    if (!dB) return LOQT_INVALID_ARG;
+    if (dB_dtype != LOQT_F32 && dB_dtype != LOQT_BF16) return LOQT_INVALID_ARG;
+    if (ld_dB < in) return LOQT_BAD_SHAPE;
+    if (!aligned(dB, dB_dtype == LOQT_BF16 ? 2 : 4)) return LOQT_MISALIGNED;
+    if (!ws) return LOQT_INVALID_ARG;
+    if (!aligned(ws, 256)) return LOQT_MISALIGNED;
+    if (ws_bytes < loqt_workspace_bytes(LOQT_OP_BWD, T, out, in, r)) return LOQT_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int64_t ld_z = (int64_t)round_up(r, 8);
+    loqt_bf16* Z = reinterpret_cast<loqt_bf16*>(ws);
+    float* partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + bwd_z_bytes(T, r));
+
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    // Z = s dy deq(P)
+    p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+    p.B[0] = nf4_operand(Pq, (int)r, (int)out);  // P is out x r: K x rows
+    p.M = (int)T;
+    p.N = (int)r;
+    p.alpha = s;
+    p.C = Z;
+    p.ldc = ld_z;
+    LOQT_HIP(launch_gemm(GEMM_Z, p, st));
+    if (dx) {
+        // dx = dy deq(W) + Z B
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+        p.B[0] = nf4_operand(Wq, (int)in, (int)out);  // W is out x in: K x rows
+        p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
+        p.B[1] = bf16_operand(B, ld_B, (int)in, (int)r);  // B is r x in: K x rows
+        p.M = (int)T;
+        p.N = (int)in;
+        p.alpha = 1.0f;
+        p.C = dx;
+        p.ldc = ld_dx;
+        LOQT_HIP(launch_gemm(GEMM_DX, p, st));
+    }
+    // dB = Z^T x, contraction over T split into a fixed number of slices
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(Z, ld_z, (int)r, (int)T);   // Z is T x r: K x rows
+    p.B[0] = bf16_operand(x, ld_x, (int)in, (int)T);  // x is T x in: K x rows
+    p.M = (int)r;
+    p.N = (int)in;
+    p.alpha = 1.0f;
+    p.C = partials;
+    p.splits = gemm_db_splits(T, r, in);
+    LOQT_HIP(launch_gemm(GEMM_DB, p, st));
+    LOQT_HIP(launch_reduce_db(partials, p.splits, r, in, dB, dB_dtype, ld_dB, accumulate, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_merge_requant(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                               const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, void* ws,
+                               size_t ws_bytes, void* hip_stream) {
+    (void)ws;
+    (void)ws_bytes;
+    LOQT_TRY(check_merge(Wq, codes_out, absmax_out, Pq, B, ld_B));
+    return merge_checked(Wq, codes_out, absmax_out, Pq, B, ld_B, s, (hipStream_t)hip_stream);
+}
+
+loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc* descs, void* ws, size_t ws_bytes,
+                                       void* hip_stream) {
+    (void)ws;
+    (void)ws_bytes;
+    if (n_layers < 0 || (n_layers > 0 && !descs)) return LOQT_INVALID_ARG;
+    for (int i = 0; i < n_layers; ++i)
+        LOQT_TRY(check_merge(&descs[i].Wq, descs[i].codes_out, descs[i].absmax_out, &descs[i].Pq, descs[i].B,
+                             descs[i].ld_B));
+    for (int i = 0; i < n_layers; ++i)
+        LOQT_TRY(merge_checked(&descs[i].Wq, descs[i].codes_out, descs[i].absmax_out, &descs[i].Pq, descs[i].B,
+                               descs[i].ld_B, descs[i].s, (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+void loqt_timing_enable(int on) {
+    if (on) {
+        if (!g_timing.begin) {
+            g_timing.begin = new hipEvent_t[LOQT_TIMING_MAX_EVENTS];
+            g_timing.end = new hipEvent_t[LOQT_TIMING_MAX_EVENTS];
+            g_timing.slot = new int[LOQT_TIMING_MAX_EVENTS];
+        }
+        g_timing.n = 0;
+        g_timing.on = true;
+    } else {
+        g_timing.on = false;
+    }
+}
+
+int loqt_timing_slots(void) { return SLOT_COUNT; }
+
+loqt_status loqt_timing_read(int slot, const char** name, int64_t* launches, double* total_ms) {
+    if (slot < 0 || slot >= SLOT_COUNT || !name || !launches || !total_ms) return LOQT_INVALID_ARG;
+    *name = kSlotNames[slot];
+    *launches = 0;
+    *total_ms = 0.0;
+    for (int i = 0; i < g_timing.n; ++i) {
+        if (g_timing.slot[i] != slot) continue;
+        if (hipEventSynchronize(g_timing.end[i]) != hipSuccess) return LOQT_LAUNCH_FAILED;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_timing.begin[i], g_timing.end[i]) != hipSuccess) return LOQT_LAUNCH_FAILED;
+        *launches += 1;
+        *total_ms += ms;
+    }
+    return LOQT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,139 @@
+// NF4 block codec kernels (paper sec. 5.1): stand-alone quantise and dequantise.
+// Both are pure HBM streams: 4 + 0.5625 bytes per element for the encoder,
+// 0.5625 + 2 (bf16) or 4 (fp32) for the decoder.
+#include "loqt_internal.h"
+
+namespace loqt {
+
+// ---------------------------------------------------------------------------------------
+// quantise: 8 lanes per block of 64, 8 consecutive elements per lane (two 16-byte loads,
+// one 4-byte store).  The block maximum is a 3-step butterfly inside each group of 8 lanes.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void nf4_quantize_kernel(const float* __restrict__ w, int64_t rows,
+                                                           int cols, int64_t ld_w,
+                                                           uint8_t* __restrict__ codes,
+                                                           float* __restrict__ absmax, int64_t ld_q) {
+    const int nbr = (int)(ld_q >> 6);  // blocks per row, padding included
+    const int64_t nblocks = rows * nbr;
+    const int sub = threadIdx.x & 7;
+    for (int64_t blk = (int64_t)blockIdx.x * 32 + (threadIdx.x >> 3); blk < nblocks;
+         blk += (int64_t)gridDim.x * 32) {
+        const int64_t row = blk / nbr;
+        const int bcol = (int)(blk - row * nbr);
+        const int j0 = bcol * 64 + sub * 8;
+        const float* src = w + row * ld_w + j0;
+        float v[8];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j0 + 4 * h < cols) f = *reinterpret_cast<const float4*>(src + 4 * h);
+            v[4 * h + 0] = (j0 + 4 * h + 0 < cols) ? f.x : 0.f;
+            v[4 * h + 1] = (j0 + 4 * h + 1 < cols) ? f.y : 0.f;
+            v[4 * h + 2] = (j0 + 4 * h + 2 < cols) ? f.z : 0.f;
+            v[4 * h + 3] = (j0 + 4 * h + 3 < cols) ? f.w : 0.f;
+        }
+        float m = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf(v[e]));
+        m = fmaxf(m, __shfl_xor(m, 1));
+        m = fmaxf(m, __shfl_xor(m, 2));
+        m = fmaxf(m, __shfl_xor(m, 4));
+        uint32_t word = 0x77777777u;
+        if (m > 0.f) {
+            Nf4Thresholds th;
+            th.set(m);
+            word = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t c = (j0 + e < cols) ? th.encode(v[e]) : 7u;
+                // element e lives in byte e/2; even e in the high nibble
+                word |= c << (8 * (e >> 1) + ((e & 1) ? 0 : 4));
+            }
+        }
+        *reinterpret_cast<uint32_t*>(codes + row * (ld_q >> 1) + (j0 >> 1)) = word;
+        if (sub == 0) absmax[row * nbr + bcol] = m;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// dequantise: 8 elements (4 code bytes) per lane.
+// ---------------------------------------------------------------------------------------
+template <int OUT_BF16>
+__global__ __launch_bounds__(256) void nf4_dequantize_kernel(const uint8_t* __restrict__ codes,
+                                                             const float* __restrict__ absmax,
+                                                             int64_t rows, int cols, int64_t ld_q,
+                                                             void* __restrict__ out, int64_t ld_out) {
+    __shared__ float lut[16];
+    if (threadIdx.x < 16) lut[threadIdx.x] = kNf4Levels[threadIdx.x];
+    __syncthreads();
+    const int gpr = (cols + 7) >> 3;  // groups of 8 elements per row
+    const int64_t ngroups = rows * gpr;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups;
+         g += (int64_t)gridDim.x * 256) {
+        const int64_t row = g / gpr;
+        const int j0 = (int)(g - row * gpr) * 8;
+        const uint32_t word = *reinterpret_cast<const uint32_t*>(codes + row * (ld_q >> 1) + (j0 >> 1));
+        const float m = absmax[row * (ld_q >> 6) + (j0 >> 6)];
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t c = (word >> (8 * (e >> 1) + ((e & 1) ? 0 : 4))) & 15u;
+            v[e] = m * lut[c];
+        }
+        if (OUT_BF16) {
+            uint16_t* dst = reinterpret_cast<uint16_t*>(out) + row * ld_out + j0;
+            if (j0 + 8 <= cols) {
+                uint4 o;
+                o.x = pack_bf16(v[0], v[1]);
+                o.y = pack_bf16(v[2], v[3]);
+                o.z = pack_bf16(v[4], v[5]);
+                o.w = pack_bf16(v[6], v[7]);
+                *reinterpret_cast<uint4*>(dst) = o;
+            } else {
+                for (int e = 0; e < 8 && j0 + e < cols; ++e)
+                    dst[e] = (uint16_t)(pack_bf16(v[e], 0.f) & 0xffffu);
+            }
+        } else {
+            float* dst = reinterpret_cast<float*>(out) + row * ld_out + j0;
+            if (j0 + 8 <= cols) {
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+            } else {
+                for (int e = 0; e < 8 && j0 + e < cols; ++e) dst[e] = v[e];
+            }
+        }
+    }
+}
+
+static int grid_for(int64_t work_items, int per_block) {
+    int64_t b = (work_items + per_block - 1) / per_block;
+    const int64_t cap = 256 * 64;  // enough waves to saturate HBM; the kernels grid-stride
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t ld_w, uint8_t* codes,
+                           float* absmax, int64_t ld_q, hipStream_t st) {
+    TimedLaunch tl(SLOT_QUANTIZE, st);
+    const int64_t nblocks = rows * (ld_q >> 6);
+    hipLaunchKernelGGL(nf4_quantize_kernel, dim3(grid_for(nblocks, 32)), dim3(256), 0, st, w, rows,
+                       (int)cols, ld_w, codes, absmax, ld_q);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
+                             int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st) {
+    TimedLaunch tl(SLOT_DEQUANTIZE, st);
+    const int64_t ngroups = rows * ((cols + 7) >> 3);
+    const int grid = grid_for(ngroups, 256);
+    if (out_dtype == LOQT_BF16)
+        hipLaunchKernelGGL(nf4_dequantize_kernel<1>, dim3(grid), dim3(256), 0, st, codes, absmax, rows,
+                           (int)cols, ld_q, out, ld_out);
+    else
+        hipLaunchKernelGGL(nf4_dequantize_kernel<0>, dim3(grid), dim3(256), 0, st, codes, absmax, rows,
+                           (int)cols, ld_q, out, ld_out);
+    return hipGetLastError();
+}
+
+}  // namespace loqt
