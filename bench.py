@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoQT hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input for one
+transformer block: loqt_linear_fwd + loqt_linear_bwd for each of the 7 projections, then the
+merge + NF4 requantisation of all 7 weights (loqt_merge_requant_batched).  Inputs are resident
+in HBM before the timed region.  Prints ONE JSON line (see README / DESIGN for the fields).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b_block] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+METRIC = "LoQT NF4 linear fwd+bwd TFLOP/s at 7B shapes; merge+requant GB/s"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="7b_block")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, seed, sample_T):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
+    forward + backward of the first projection on `sample_T` tokens (each output row depends
+    only on its own token, so a token subset is the same arithmetic per token)."""
+    import numpy as np
+    from oracle import loqt_oracle as O
+    from paper_2405_16528_amd import synth
+    name, out, inp = wl.projections[0]
+    lay = synth.make_layer(wl.name, name, out, inp, wl.r, sample_T, seed)
+    Wq, Pq = O.nf4_quantize(lay.W), O.nf4_quantize(lay.P)
+    t0 = time.perf_counter()
+    O.loqt_linear_fwd(lay.x, Wq, Pq, lay.B, 1.0)
+    O.loqt_linear_bwd(lay.dy, lay.x, Wq, Pq, lay.B, 1.0)
+    dt = time.perf_counter() - t0
+    flops = synth.flops_fwd(sample_T, out, inp, wl.r) + synth.flops_bwd(sample_T, out, inp, wl.r)
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores = os.cpu_count()
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env:
+        cores = min(cores, int(env))
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"fwd+bwd of projection '{name}' ({out}x{inp}, r={wl.r}) of {wl.name} on {sample_T} of "
+                      f"{wl.T} tokens, numpy float64, {dt:.2f} s",
+            "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on ONE GPU only (got --gpus {args.gpus}); "
+              "there is no multi-GPU path to time.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2405_16528_amd import binding as L
+    from paper_2405_16528_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    T, r = wl.T, wl.r
+    dev = "cuda"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+
+    def pitch8(n):
+        return (n + 7) // 8 * 8
+
+    def randn_bf16(rows, cols, sigma):
+        buf = torch.empty((rows, pitch8(cols)), dtype=torch.float32, device=dev)
+        buf.normal_(0.0, sigma, generator=gen)
+        return buf.to(torch.bfloat16)[:, :cols]
+
+    layers = []
+    ws_bytes = 256
+    for (name, out, inp) in wl.projections:
+        # W and P are drawn on the host by the seeded generator (P needs a QR), x / dy / B on the device
+        W = synth.normal_f32(synth.rng_for(args.seed, wl.name, 0, name, "W"), (out, inp), 0.02)
+        P = synth.orthonormal_f32(synth.rng_for(args.seed, wl.name, 0, name, "P"), out, r)
+        Wd = torch.from_numpy(W).to(dev)
+        if inp % 4:
+            Wp = torch.zeros((out, (inp + 3) // 4 * 4), dtype=torch.float32, device=dev)
+            Wp[:, :inp] = Wd
+            Wd = Wp[:, :inp]
+        Wq = L.nf4_quantize(Wd)
+        Pq = L.nf4_quantize(torch.from_numpy(P).to(dev))
+        del Wd
+        lay = dict(name=name, out=out, inp=inp, Wq=Wq, Pq=Pq,
+                   Wq_out=L.NF4Tensor.empty(out, inp),
+                   B=randn_bf16(r, inp, 1e-3), x=randn_bf16(T, inp, 1.0), dy=randn_bf16(T, out, 1e-2),
+                   y=torch.empty((T, pitch8(out)), dtype=torch.bfloat16, device=dev)[:, :out],
+                   dx=torch.empty((T, pitch8(inp)), dtype=torch.bfloat16, device=dev)[:, :inp],
+                   dB=torch.empty((r, inp), dtype=torch.float32, device=dev))
+        layers.append(lay)
+        ws_bytes = max(ws_bytes, L.loqt_workspace_bytes(L.OP_BWD, T, out, inp, r),
+                       L.loqt_workspace_bytes(L.OP_FWD, T, out, inp, r))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    descs = L.make_merge_descs([(l["Wq"], l["Wq_out"], l["Pq"], l["B"], 1.0) for l in layers])
+    torch.cuda.synchronize()
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+    phase_events = []
+
+    def step(record=False):
+        if record:
+            e0, e1, e2 = ev(), ev(), ev()
+            e0.record()
+        for l in layers:
+            L.loqt_linear_fwd(l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["y"], ws)
+            L.loqt_linear_bwd(l["dy"], l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["dx"], l["dB"], False, ws)
+        if record:
+            e1.record()
+        L.loqt_merge_requant_batched(descs)
+        if record:
+            e2.record()
+            phase_events.append((e0, e1, e2))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    L.timing_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(record=True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    L.timing_enable(False)
+    kt = L.timing_read()
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    f_fb = sum(synth.flops_fwd(T, o, i, r) + synth.flops_bwd(T, o, i, r) for (_, o, i) in wl.projections)
+    f_mg = sum(synth.flops_merge(o, i, r) for (_, o, i) in wl.projections)
+    b_mg = sum(synth.bytes_merge(o, i, r) for (_, o, i) in wl.projections)
+    ms_fb = sum(a.elapsed_time(b) for (a, b, _) in phase_events) / args.steps
+    ms_mg = sum(b.elapsed_time(c) for (_, b, c) in phase_events) / args.steps
+
+    # algorithmic flops of each GEMM kernel over one step (factored form)
+    kflops = {
+        "gemm_u": sum(2 * T * i * r for (_, o, i) in wl.projections),
+        "gemm_y": sum(2 * T * o * (i + r) for (_, o, i) in wl.projections),
+        "gemm_z": sum(2 * T * o * r for (_, o, i) in wl.projections),
+        "gemm_dx": sum(2 * T * i * (o + r) for (_, o, i) in wl.projections),
+        "gemm_db": sum(2 * T * r * i for (_, o, i) in wl.projections),
+        "merge_requant": f_mg,
+    }
+    kernels = {}
+    for name, (n, ms) in kt.items():
+        if n == 0:
+            continue
+        ent = {"launches_per_step": n / args.steps, "ms_per_step": ms / args.steps, "avg_ms": ms / n}
+        if name in kflops:
+            ent["tflops"] = kflops[name] * args.steps / (ms * 1e-3) / 1e12
+        kernels[name] = ent
+    dom = max((k for k in kernels if k in kflops and k != "merge_requant"), key=lambda k: kernels[k]["ms_per_step"])
+    dk = kernels[dom]
+    n_launch = dk["launches_per_step"]
+    roofline = {
+        "kernel": dom, "bound": "mfma",
+        "achieved": dk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": dk["tflops"] / PEAK_BF16_TFLOPS,
+        "flops_per_launch": kflops[dom] / n_launch, "avg_launch_ms": dk["avg_ms"],
+        "traffic": None,
+    }
+    # the merge is bound by max(HBM stream, rank-r bf16 product); report both views
+    mk = kernels.get("merge_requant")
+    merge = None
+    if mk:
+        t_hbm = b_mg / (PEAK_HBM_GBS * 1e9) * 1e3
+        t_mfma = f_mg / (PEAK_BF16_TFLOPS * 1e12) * 1e3
+        merge = {"ms_per_step": mk["ms_per_step"], "algorithmic_GBs": b_mg / (mk["ms_per_step"] * 1e-3) / 1e9,
+                 "tflops": mk["tflops"], "t_hbm_ms": t_hbm, "t_mfma_ms": t_mfma,
+                 "frac_of_binding_roof": max(t_hbm, t_mfma) / mk["ms_per_step"],
+                 "frac_of_hbm_peak": t_hbm / mk["ms_per_step"]}
+
+    out = {
+        "metric": METRIC,
+        "value": (f_fb + f_mg) / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "tokens": T, "rank": r,
+                   "projections": [f"{n}:{o}x{i}" for (n, o, i) in wl.projections],
+                   "step": "7x(loqt_linear_fwd + loqt_linear_bwd) + batched merge/requant of the block"},
+        "fwd_bwd": {"tflops": f_fb / (ms_fb * 1e-3) / 1e12, "ms_per_step": ms_fb,
+                    "frac_of_bf16_peak": f_fb / (ms_fb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+        "merge": merge,
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.seed, min(args.cpu_sample_tokens, T))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

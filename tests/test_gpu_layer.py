@@ -170,7 +170,9 @@ def test_merge_large_update_parity():
     c, a, _, _ = G.nf4_host(m)
     rate = _merge_policy_check(c, a, Wq, Pq, lay.B, 1.0)
     assert not np.array_equal(a, Wq[1])
-    assert rate <= 2e-3
+    # the rate scales with |update| / absmax: 2^-9 relative error of a product as large as the
+    # weight moves t by ~5e-4, and about 15 thresholds per unit of t are in reach
+    assert rate <= 1e-2
 
 
 def test_merge_exact_case_bit_exact():
