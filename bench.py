@@ -115,7 +115,8 @@ def main():
                    dB=torch.empty((r, inp), dtype=torch.float32, device=dev))
         layers.append(lay)
         ws_bytes = max(ws_bytes, L.loqt_workspace_bytes(L.OP_BWD, T, out, inp, r),
-                       L.loqt_workspace_bytes(L.OP_FWD, T, out, inp, r))
+                       L.loqt_workspace_bytes(L.OP_FWD, T, out, inp, r),
+                       L.loqt_workspace_bytes(L.OP_MERGE, T, out, inp, r))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     descs = L.make_merge_descs([(l["Wq"], l["Wq_out"], l["Pq"], l["B"], 1.0) for l in layers])
     torch.cuda.synchronize()
@@ -132,7 +133,7 @@ def main():
             L.loqt_linear_bwd(l["dy"], l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["dx"], l["dB"], False, ws)
         if record:
             e1.record()
-        L.loqt_merge_requant_batched(descs)
+        L.loqt_merge_requant_batched(descs, ws)
         if record:
             e2.record()
             phase_events.append((e0, e1, e2))

@@ -99,10 +99,12 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
 /*
  * Bytes of device workspace the given operation needs for these sizes (0 is possible).
  * The workspace must be 256-byte aligned; its contents are scratch.  Two calls that share a
- * workspace must be ordered on the same stream.
- *   FWD  : U = s x B^T                       (T x r bf16)
- *   BWD  : Z = s dy deq(P_q) (T x r bf16) and the split-K partial sums of dB (fp32)
- *   MERGE: none
+ * workspace must be ordered on the same stream.  The figure covers both implementations (see
+ * loqt_set_path), so it does not depend on the path option:
+ *   FWD  : U = s x B^T (T x r bf16); pre-pass path: + bf16 copies of deq(W_q), deq(P_q)
+ *   BWD  : Z = s dy deq(P_q) (T x r bf16), split-K partial sums of dB (fp32); pre-pass path:
+ *          + Z^T, deq(W_q)^T, deq(P_q)^T, B^T, x^T in bf16
+ *   MERGE: pre-pass path: bf16 deq(P_q) and B^T (T is ignored)
  */
 size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r);
 
@@ -165,6 +167,20 @@ typedef struct loqt_merge_desc {
  */
 loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *descs,
                                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Implementation choice (process-wide; not thread-safe; default LOQT_PATH_AUTO).
+ *   LOQT_PATH_FUSED  : NF4 codes are expanded inside the GEMMs' operand staging (global memory
+ *                      -> registers -> LDS), no extra pass over the weights.
+ *   LOQT_PATH_PREPASS: NF4 operands are expanded to bf16 in the workspace by one streaming pass
+ *                      per call (transposed where the product needs it), then every product is
+ *                      a K-contiguous bf16 GEMM fed by direct global->LDS loads.
+ *   LOQT_PATH_AUTO   : pre-pass when at least 1024 rows (tokens; `in` for the merge) share each
+ *                      weight tile, fused below that.
+ * Both compute the same quantities; results differ only in fp32 summation order.
+ */
+enum { LOQT_PATH_AUTO = 0, LOQT_PATH_FUSED = 1, LOQT_PATH_PREPASS = 2 };
+loqt_status loqt_set_path(int path);
 
 /*
  * Optional per-kernel timing (diagnostics for benchmarks; off by default).

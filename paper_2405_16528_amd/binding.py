@@ -23,6 +23,7 @@ lib = C.CDLL(_LIB_PATH)
 
 F32, BF16 = 0, 1
 OP_FWD, OP_BWD, OP_MERGE = 0, 1, 2
+PATH_AUTO, PATH_FUSED, PATH_PREPASS = 0, 1, 2
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
                 4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
 
@@ -63,6 +64,8 @@ lib.loqt_merge_requant.restype = _i
 lib.loqt_merge_requant.argtypes = [_P(NF4MatC), _vp, _vp, _P(NF4MatC), _vp, _i64, _f, _vp, _sz, _vp]
 lib.loqt_merge_requant_batched.restype = _i
 lib.loqt_merge_requant_batched.argtypes = [_i, _P(MergeDescC), _vp, _sz, _vp]
+lib.loqt_set_path.restype = _i
+lib.loqt_set_path.argtypes = [_i]
 lib.loqt_timing_enable.restype = None
 lib.loqt_timing_enable.argtypes = [_i]
 lib.loqt_timing_slots.restype = _i
@@ -149,11 +152,23 @@ def loqt_linear_bwd(dy, x, Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, dx, dB, ac
     return dx, dB
 
 
-def loqt_merge_requant(Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, out: Optional[NF4Tensor] = None) -> NF4Tensor:
-    """out=None merges in place."""
+def workspace(op: int, T: int, out: int, inp: int, r: int, device="cuda") -> torch.Tensor:
+    """A scratch buffer of loqt_workspace_bytes(...) bytes (torch's allocations are 256-byte aligned)."""
+    return torch.empty(max(loqt_workspace_bytes(op, T, out, inp, r), 256), dtype=torch.uint8, device=device)
+
+
+def _ws_args(ws):
+    return (None, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+def loqt_merge_requant(Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, out: Optional[NF4Tensor] = None,
+                       ws: Optional[torch.Tensor] = None) -> NF4Tensor:
+    """out=None merges in place; ws=None allocates the workspace for this call."""
     out = out or Wq
+    if ws is None:
+        ws = workspace(OP_MERGE, 0, Wq.rows, Wq.cols, Pq.cols, Wq.codes.device)
     _check(lib.loqt_merge_requant(C.byref(Wq.c()), out.codes.data_ptr(), out.absmax.data_ptr(), C.byref(Pq.c()),
-                                  B.data_ptr(), _pitch(B), s, None, 0, _stream()), "loqt_merge_requant")
+                                  B.data_ptr(), _pitch(B), s, *_ws_args(ws), _stream()), "loqt_merge_requant")
     return out
 
 
@@ -168,8 +183,19 @@ def make_merge_descs(layers):
     return arr
 
 
-def loqt_merge_requant_batched(descs) -> None:
-    _check(lib.loqt_merge_requant_batched(len(descs), descs, None, 0, _stream()), "loqt_merge_requant_batched")
+def merge_descs_workspace_bytes(descs) -> int:
+    return max([loqt_workspace_bytes(OP_MERGE, 0, d.Wq.rows, d.Wq.cols, d.Pq.cols) for d in descs] + [256])
+
+
+def loqt_merge_requant_batched(descs, ws: Optional[torch.Tensor] = None) -> None:
+    if ws is None:
+        ws = torch.empty(merge_descs_workspace_bytes(descs), dtype=torch.uint8, device="cuda")
+    _check(lib.loqt_merge_requant_batched(len(descs), descs, *_ws_args(ws), _stream()), "loqt_merge_requant_batched")
+
+
+def set_path(path: int) -> None:
+    """PATH_AUTO, PATH_FUSED or PATH_PREPASS (process-wide)."""
+    _check(lib.loqt_set_path(path), "loqt_set_path")
 
 
 def timing_enable(on: bool) -> None:

@@ -18,7 +18,7 @@ struct TimingState {
     int created = 0;
 } g_timing;
 const char* kSlotNames[SLOT_COUNT] = {"nf4_quantize", "nf4_dequantize", "gemm_u",   "gemm_y",      "gemm_z",
-                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant"};
+                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant", "prepass"};
 }  // namespace
 
 TimedLaunch::TimedLaunch(int slot_, hipStream_t s) : stream(s), slot(slot_), idx(-1) {
@@ -80,7 +80,67 @@ loqt_status check_layer(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const vo
     return LOQT_OK;
 }
 
-size_t bwd_z_bytes(int64_t T, int64_t r) { return round_up((size_t)T * (size_t)round_up(r, 8) * 2, 256); }
+// ---------------------------------------------------------------------------------------
+// Two implementations of every call: "fused" (NF4 expanded inside the GEMM's operand staging,
+// no pre-pass; best when few tokens share a weight tile) and "prepass" (NF4 expanded to bf16
+// once per call, then plain NT GEMMs; best from about a thousand tokens up).
+// ---------------------------------------------------------------------------------------
+int g_path = LOQT_PATH_AUTO;
+
+bool use_prepass(int64_t rows_sharing_weights) {
+    if (g_path == LOQT_PATH_FUSED) return false;
+    if (g_path == LOQT_PATH_PREPASS) return true;
+    return rows_sharing_weights >= 1024;
+}
+
+inline size_t bf16_bytes(int64_t rows, int64_t cols) {
+    return round_up((size_t)rows * (size_t)round_up(cols, 8) * 2, 256);
+}
+size_t bwd_z_bytes(int64_t T, int64_t r) { return bf16_bytes(T, r); }
+
+// index arithmetic of the NT kernel: 32-bit row offsets are not used, but rows * pitch must
+// stay below 2^40 elements; the host checks shapes against kMaxDim only.
+struct FwdWs {  // prepass forward
+    size_t U, Wb, Pb, total;
+    FwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
+        U = 0;
+        Wb = U + bf16_bytes(T, r);
+        Pb = Wb + bf16_bytes(out, in);
+        total = Pb + bf16_bytes(out, r);
+    }
+};
+struct BwdWs {  // prepass backward
+    size_t Z, Zt, Wt, Pt, Bt, xt, partials, total;
+    int splits;
+    int64_t ldp;
+    BwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
+        Z = 0;
+        Zt = Z + bf16_bytes(T, r);
+        Pt = Zt + bf16_bytes(r, T);
+        Wt = Pt + bf16_bytes(r, out);
+        Bt = Wt + bf16_bytes(in, out);
+        xt = Bt + bf16_bytes(in, r);
+        partials = xt + bf16_bytes(in, T);
+        ldp = (int64_t)round_up(in, 4);
+        // split the contraction over T until the grid fills the machine twice over
+        const int64_t tiles = ((r + 255) / 256) * ((in + 255) / 256);
+        int64_t s = (512 + tiles - 1) / tiles;
+        const int64_t max_s = (T + 511) / 512;
+        if (s > max_s) s = max_s;
+        if (s < 1) s = 1;
+        if (s > 16) s = 16;
+        splits = (int)s;
+        total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
+    }
+};
+struct MergeWs {  // prepass merge
+    size_t Pb, Bt, total;
+    MergeWs(int64_t out, int64_t in, int64_t r) {
+        Pb = 0;
+        Bt = Pb + bf16_bytes(out, r);
+        total = Bt + bf16_bytes(in, r);
+    }
+};
 
 Operand nf4_operand(const loqt_nf4_mat* m, int rows, int K) {
     Operand o;
@@ -106,18 +166,16 @@ Operand no_operand() {
     return o;
 }
 
-loqt_status merge_checked(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
-                          const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
-                          hipStream_t st) {
+loqt_status merge_fused(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                        const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, hipStream_t st) {
     const int out = (int)Wq->rows, in = (int)Wq->cols, r = (int)Pq->cols;
     GemmParams p;
     memset(&p, 0, sizeof(p));
-    // transposed product: rows of the tile run along `in`
+    // transposed product: rows of the tile run along `in`; the grid reaches the padding
+    // columns cols..ld-1 as well (operand rows past `in` read as zero)
     p.A[0] = bf16_operand(B, ld_B, in, r);  // B is r x in: K x rows
     p.B[0] = nf4_operand(Pq, out, r);       // P is out x r: rows x K
-    p.A[1] = no_operand();
-    p.B[1] = no_operand();
-    p.M = in;
+    p.M = (int)Wq->ld;
     p.N = out;
     p.alpha = s;
     p.w_codes = Wq->codes;
@@ -126,10 +184,52 @@ loqt_status merge_checked(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* abs
     p.out_absmax = absmax_out;
     p.w_ld = Wq->ld;
     p.w_cols = in;
-    // the tile grid must reach the padding columns cols..ld-1 as well
-    p.M = (int)Wq->ld;
-    p.A[0].rows = in;
     LOQT_HIP(launch_gemm(GEMM_MERGE, p, st));
+    return LOQT_OK;
+}
+
+loqt_status merge_prepass(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                          const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, void* ws,
+                          hipStream_t st) {
+    const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
+    const MergeWs L(out, in, r);
+    char* base = reinterpret_cast<char*>(ws);
+    uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
+    uint16_t* Bt = reinterpret_cast<uint16_t*>(base + L.Bt);
+    const int64_t ldr = (int64_t)round_up(r, 8);
+    LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ldr, st, SLOT_PREPASS));
+    LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ldr, st));
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(Pb, ldr, (int)out, (int)r);  // rows of the tile are rows of W
+    p.B[0] = bf16_operand(Bt, ldr, (int)in, (int)r);   // columns run along `in`
+    p.M = (int)out;
+    p.N = (int)Wq->ld;  // reach the padding columns (operand rows past `in` are never used)
+    p.alpha = s;
+    p.w_codes = Wq->codes;
+    p.w_absmax = Wq->absmax;
+    p.out_codes = codes_out;
+    p.out_absmax = absmax_out;
+    p.w_ld = Wq->ld;
+    p.w_cols = (int)in;
+    LOQT_HIP(launch_gemm_nt(SLOT_MERGE, EPI_MERGE, p, st));
+    return LOQT_OK;
+}
+
+size_t merge_ws_bytes(int64_t out, int64_t in, int64_t r) { return MergeWs(out, in, r).total; }
+
+loqt_status merge_checked(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                          const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, void* ws,
+                          hipStream_t st) {
+    if (use_prepass(Wq->cols)) return merge_prepass(Wq, codes_out, absmax_out, Pq, B, ld_B, s, ws, st);
+    return merge_fused(Wq, codes_out, absmax_out, Pq, B, ld_B, s, st);
+}
+
+loqt_status check_merge_ws(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, void* ws, size_t ws_bytes) {
+    if (!use_prepass(Wq->cols)) return LOQT_OK;
+    if (!ws) return LOQT_INVALID_ARG;
+    if (!aligned(ws, 256)) return LOQT_MISALIGNED;
+    if (ws_bytes < merge_ws_bytes(Wq->rows, Wq->cols, Pq->cols)) return LOQT_WORKSPACE_TOO_SMALL;
     return LOQT_OK;
 }
 
@@ -193,12 +293,20 @@ loqt_status nf4_dequantize(const uint8_t* codes, const float* absmax, int64_t ro
 }
 
 size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r) {
-    (void)out;
-    if (T <= 0 || in <= 0 || r <= 0) return 0;
+    if (out <= 0 || in <= 0 || r <= 0) return 0;
+    // enough for either implementation, so that the size does not depend on the path option
     switch (op) {
-        case LOQT_OP_FWD: return bwd_z_bytes(T, r);
-        case LOQT_OP_BWD:
-            return bwd_z_bytes(T, r) + round_up((size_t)gemm_db_splits(T, r, in) * (size_t)r * (size_t)in * 4, 256);
+        case LOQT_OP_FWD: {
+            if (T <= 0) return 0;
+            return FwdWs(T, out, in, r).total;  // the fused path needs only its first part (U)
+        }
+        case LOQT_OP_BWD: {
+            if (T <= 0) return 0;
+            const size_t fused = bwd_z_bytes(T, r) + round_up((size_t)gemm_db_splits(T, r, in) * (size_t)r * (size_t)in * 4, 256);
+            const size_t pre = BwdWs(T, out, in, r).total;
+            return fused > pre ? fused : pre;
+        }
+        case LOQT_OP_MERGE: return merge_ws_bytes(out, in, r);
         default: return 0;
     }
 }
@@ -216,8 +324,41 @@ loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
     hipStream_t st = (hipStream_t)hip_stream;
     const int64_t ld_u = (int64_t)round_up(r, 8);
     loqt_bf16* U = reinterpret_cast<loqt_bf16*>(ws);
-
     GemmParams p;
+
+    if (use_prepass(T)) {
+        const FwdWs L(T, out, in, r);
+        char* base = reinterpret_cast<char*>(ws);
+        uint16_t* Wb = reinterpret_cast<uint16_t*>(base + L.Wb);
+        uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
+        const int64_t ldw = (int64_t)round_up(in, 8);
+        LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wb, LOQT_BF16, ldw, st, SLOT_PREPASS));
+        LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_u, st, SLOT_PREPASS));
+        // U = s x B^T
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+        p.B[0] = bf16_operand(B, ld_B, (int)r, (int)in);
+        p.M = (int)T;
+        p.N = (int)r;
+        p.alpha = s;
+        p.C = U;
+        p.ldc = ld_u;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_U, EPI_BF16, p, st));
+        // y = x deq(W)^T + U deq(P)^T
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+        p.B[0] = bf16_operand(Wb, ldw, (int)out, (int)in);
+        p.A[1] = bf16_operand(U, ld_u, (int)T, (int)r);
+        p.B[1] = bf16_operand(Pb, ld_u, (int)out, (int)r);
+        p.M = (int)T;
+        p.N = (int)out;
+        p.alpha = 1.0f;
+        p.C = y;
+        p.ldc = ld_y;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, p, st));
+        return LOQT_OK;
+    }
+
     memset(&p, 0, sizeof(p));
     // U = s x B^T
     p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
@@ -265,6 +406,59 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
     float* partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + bwd_z_bytes(T, r));
 
     GemmParams p;
+    if (use_prepass(T)) {
+        const BwdWs L(T, out, in, r);
+        char* base = reinterpret_cast<char*>(ws);
+        uint16_t* Zt = reinterpret_cast<uint16_t*>(base + L.Zt);
+        uint16_t* Pt = reinterpret_cast<uint16_t*>(base + L.Pt);
+        uint16_t* Wt = reinterpret_cast<uint16_t*>(base + L.Wt);
+        uint16_t* Bt = reinterpret_cast<uint16_t*>(base + L.Bt);
+        uint16_t* xt = reinterpret_cast<uint16_t*>(base + L.xt);
+        float* part = reinterpret_cast<float*>(base + L.partials);
+        const int64_t ldo = (int64_t)round_up(out, 8), ldT = (int64_t)round_up(T, 8);
+        // Z = s dy deq(P): B operand is deq(P)^T, r x out
+        LOQT_HIP(launch_dequant_transpose(Pq->codes, Pq->absmax, out, r, Pq->ld, Pt, ldo, st));
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+        p.B[0] = bf16_operand(Pt, ldo, (int)r, (int)out);
+        p.M = (int)T;
+        p.N = (int)r;
+        p.alpha = s;
+        p.C = Z;
+        p.ldc = ld_z;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, p, st));
+        if (dx) {
+            // dx = dy deq(W) + Z B: B operands are deq(W)^T (in x out) and B^T (in x r)
+            LOQT_HIP(launch_dequant_transpose(Wq->codes, Wq->absmax, out, in, Wq->ld, Wt, ldo, st));
+            LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ld_z, st));
+            memset(&p, 0, sizeof(p));
+            p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+            p.B[0] = bf16_operand(Wt, ldo, (int)in, (int)out);
+            p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
+            p.B[1] = bf16_operand(Bt, ld_z, (int)in, (int)r);
+            p.M = (int)T;
+            p.N = (int)in;
+            p.alpha = 1.0f;
+            p.C = dx;
+            p.ldc = ld_dx;
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, p, st));
+        }
+        // dB = Z^T x: operands Z^T (r x T) and x^T (in x T), contraction over T in slices
+        LOQT_HIP(launch_transpose_bf16(Z, T, r, ld_z, Zt, ldT, st));
+        LOQT_HIP(launch_transpose_bf16(x, T, in, ld_x, xt, ldT, st));
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(Zt, ldT, (int)r, (int)T);
+        p.B[0] = bf16_operand(xt, ldT, (int)in, (int)T);
+        p.M = (int)r;
+        p.N = (int)in;
+        p.alpha = 1.0f;
+        p.C = part;
+        p.ldc = L.ldp;
+        p.splits = L.splits;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DB, EPI_F32_SPLITK, p, st));
+        LOQT_HIP(launch_reduce_db(part, L.splits, r, in, L.ldp, dB, dB_dtype, ld_dB, accumulate, st));
+        return LOQT_OK;
+    }
     memset(&p, 0, sizeof(p));
     // Z = s dy deq(P)
     p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
@@ -299,30 +493,36 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
     p.C = partials;
     p.splits = gemm_db_splits(T, r, in);
     LOQT_HIP(launch_gemm(GEMM_DB, p, st));
-    LOQT_HIP(launch_reduce_db(partials, p.splits, r, in, dB, dB_dtype, ld_dB, accumulate, st));
+    LOQT_HIP(launch_reduce_db(partials, p.splits, r, in, in, dB, dB_dtype, ld_dB, accumulate, st));
     return LOQT_OK;
 }
 
 loqt_status loqt_merge_requant(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
                                const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, void* ws,
                                size_t ws_bytes, void* hip_stream) {
-    (void)ws;
-    (void)ws_bytes;
     LOQT_TRY(check_merge(Wq, codes_out, absmax_out, Pq, B, ld_B));
-    return merge_checked(Wq, codes_out, absmax_out, Pq, B, ld_B, s, (hipStream_t)hip_stream);
+    LOQT_TRY(check_merge_ws(Wq, Pq, ws, ws_bytes));
+    return merge_checked(Wq, codes_out, absmax_out, Pq, B, ld_B, s, ws, (hipStream_t)hip_stream);
 }
 
 loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc* descs, void* ws, size_t ws_bytes,
                                        void* hip_stream) {
-    (void)ws;
-    (void)ws_bytes;
     if (n_layers < 0 || (n_layers > 0 && !descs)) return LOQT_INVALID_ARG;
-    for (int i = 0; i < n_layers; ++i)
+    for (int i = 0; i < n_layers; ++i) {
         LOQT_TRY(check_merge(&descs[i].Wq, descs[i].codes_out, descs[i].absmax_out, &descs[i].Pq, descs[i].B,
                              descs[i].ld_B));
+        LOQT_TRY(check_merge_ws(&descs[i].Wq, &descs[i].Pq, ws, ws_bytes));
+    }
+    // layers run back to back on one stream, so they can share the workspace
     for (int i = 0; i < n_layers; ++i)
         LOQT_TRY(merge_checked(&descs[i].Wq, descs[i].codes_out, descs[i].absmax_out, &descs[i].Pq, descs[i].B,
-                               descs[i].ld_B, descs[i].s, (hipStream_t)hip_stream));
+                               descs[i].ld_B, descs[i].s, ws, (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+loqt_status loqt_set_path(int path) {
+    if (path != LOQT_PATH_AUTO && path != LOQT_PATH_FUSED && path != LOQT_PATH_PREPASS) return LOQT_INVALID_ARG;
+    g_path = path;
     return LOQT_OK;
 }
 

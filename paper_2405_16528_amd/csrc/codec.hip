@@ -123,8 +123,8 @@ hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t l
 }
 
 hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
-                             int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st) {
-    TimedLaunch tl(SLOT_DEQUANTIZE, st);
+                             int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st, int slot) {
+    TimedLaunch tl(slot, st);
     const int64_t ngroups = rows * ((cols + 7) >> 3);
     const int grid = grid_for(ngroups, 256);
     if (out_dtype == LOQT_BF16)

@@ -386,7 +386,7 @@ __global__ __launch_bounds__(256) void loqt_gemm_kernel(const GemmParams p) {
 
 // dB = (accumulate ? dB : 0) + sum over splits of the fp32 partials, then to the output dtype
 __global__ __launch_bounds__(256) void reduce_db_kernel(const float* __restrict__ partials, int splits,
-                                                        int64_t M, int N, void* __restrict__ dB,
+                                                        int64_t M, int N, int64_t ldp, void* __restrict__ dB,
                                                         int dB_bf16, int64_t ld_dB, int accumulate) {
     const int64_t total = M * N;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
@@ -394,7 +394,7 @@ __global__ __launch_bounds__(256) void reduce_db_kernel(const float* __restrict_
         const int64_t m = idx / N;
         const int n = (int)(idx - m * N);
         float s = 0.f;
-        for (int k = 0; k < splits; ++k) s += partials[(int64_t)k * total + idx];
+        for (int k = 0; k < splits; ++k) s += partials[((int64_t)k * M + m) * ldp + n];
         if (dB_bf16) {
             uint16_t* d = reinterpret_cast<uint16_t*>(dB) + m * ld_dB + n;
             if (accumulate) s += __uint_as_float((uint32_t)(*d) << 16);
@@ -476,13 +476,13 @@ hipError_t launch_gemm(GemmId id, const GemmParams& p, hipStream_t st) {
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, void* dB,
+hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, int64_t ldp, void* dB,
                             int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st) {
     TimedLaunch tl(SLOT_REDUCE_DB, st);
     int64_t blocks = (M * N + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     hipLaunchKernelGGL(reduce_db_kernel, dim3((int)blocks), dim3(256), 0, st, partials, splits, M, (int)N,
-                       dB, dB_dtype == LOQT_BF16 ? 1 : 0, ld_dB, accumulate);
+                       ldp, dB, dB_dtype == LOQT_BF16 ? 1 : 0, ld_dB, accumulate);
     return hipGetLastError();
 }
 

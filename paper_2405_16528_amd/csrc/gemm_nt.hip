@@ -1,0 +1,356 @@
+// Fast path for large token counts: every product of the layer as a plain "NT" bf16 GEMM
+//
+//   C[M x N] = alpha * sum_seg  A_seg[M x K_seg] * B_seg[N x K_seg]^T      (fp32 accumulate)
+//
+// with both operands bf16 and contiguous along K.  NF4 operands are dequantised to bf16 once
+// per call by a streaming pre-pass (prepass.hip) instead of once per output tile; at thousands
+// of tokens that pass costs a few per cent of the GEMM and keeps every VALU and LDS cycle of the
+// inner loop for feeding the matrix cores.
+//
+// Work-group: 256 threads = 4 waves (2 x 2), tile BM x BN x 64, v_mfma_f32_32x32x16_bf16.
+//  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
+//    registers, no ds_write); two LDS stages, the loads of tile t+2 are issued as soon as the
+//    barrier of tile t has released its stage, so they have a whole tile of MFMAs to land;
+//  * 16-byte chunks of a 128-byte LDS row are XOR-swizzled; the swizzle is applied on the
+//    global side (which chunk a lane fetches), the LDS side of a direct load is lane-linear;
+//  * MFMA fragments are double-buffered in registers one k16 step ahead, reads interleaved
+//    one-to-one with the MFMAs of the running step (sched_group_barrier);
+//  * the accumulators are kept transposed (lane = row m, registers = 4 consecutive n) so the
+//    epilogues can pack along n: bf16 results are staged through LDS and leave as whole
+//    16-byte-per-lane row segments; the merge epilogue requantises 64-blocks in registers;
+//  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in 8-row groups so that the
+//    work-groups sharing an L2 also share operand panels.
+#include "loqt_internal.h"
+
+namespace loqt {
+
+namespace {
+
+constexpr int BK = 64;
+constexpr int ROWB = 128;  // bytes of one LDS row (64 bf16)
+
+#define LOQT_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+#define LOQT_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+// one MFMA, one LDS read, eight times; then the remaining eight MFMAs
+#define LOQT_SCHED_GROUP()                                        \
+    do {                                                          \
+        _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_) {        \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    \
+        }                                                         \
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);        \
+        __builtin_amdgcn_sched_barrier(0);                        \
+    } while (0)
+
+__device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
+
+__device__ __forceinline__ uint32_t nib4(uint32_t word, int e) {
+    // element e (0..3) of a 2-byte group: byte e/2, even e in the high nibble
+    return (word >> (8 * (e >> 1) + ((e & 1) ? 0 : 4))) & 15u;
+}
+
+template <int BM, int BN>
+struct NtCfg {
+    static constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 tiles per wave
+    static constexpr int WTM = BM / 2, WTN = BN / 2;   // wave tile
+    static constexpr int STAGE = (BM + BN) * ROWB;
+    static constexpr int NCH = (BM + BN) / 32;         // 16-byte chunks per thread per stage
+    static constexpr int NCHA = BM / 32;               // of which belong to A
+    static constexpr int EPITCH = WTN * 2 + 8;         // staging pitch of the bf16 epilogue
+    static constexpr int SMEM_MAIN = 2 * STAGE;
+    static constexpr int SMEM_EPI = 4 * WTM * EPITCH;
+    static constexpr int SMEM = (SMEM_MAIN > SMEM_EPI ? SMEM_MAIN : SMEM_EPI) + 64;
+};
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
+    using Cfg = NtCfg<BM, BN>;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE, NCH = Cfg::NCH, NCHA = Cfg::NCHA;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- tile of this work-group: contiguous range per XCD, 8-row groups inside
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const int per_xcd = gridDim.x >> 3;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= tiles_m * tiles_n) return;
+    constexpr int GM = 8;
+    const int gid = L / (GM * tiles_n);
+    const int first_m = gid * GM;
+    const int gsz = min(tiles_m - first_m, GM);
+    const int rem = L - gid * GM * tiles_n;
+    const int tm = first_m + rem % gsz, tn = rem / gsz;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const int nkt0 = (p.A[0].K + BK - 1) / BK;
+    const int nkt1 = (p.A[1].K + BK - 1) / BK;
+    int kt_begin = 0, kt_end = nkt0 + nkt1;
+    if (EPI == EPI_F32_SPLITK) {
+        const int per = (kt_end + p.splits - 1) / p.splits;
+        kt_begin = blockIdx.y * per;
+        kt_end = min(kt_end, kt_begin + per);
+    }
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // ---- staging: chunk i of this thread is LDS slot (i*256 + tid): row slot>>3, physical
+    // chunk slot&7, logical chunk (slot&7) ^ swz(row).  i*32 rows apart, so the chunk column
+    // is the same for every i.
+    const int r0 = tid >> 3;
+    const int kc = (tid & 7) ^ swz(r0);
+    auto stage_tile = [&](int kt, char* stage) {
+        const int seg = kt >= nkt0 ? 1 : 0;
+        const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
+        const Operand& A = p.A[seg];
+        const Operand& B = p.B[seg];
+        const int kleft = A.K - k0;
+        const uint16_t* pa = reinterpret_cast<const uint16_t*>(A.ptr) + k0 + kc * 8;
+        const uint16_t* pb = reinterpret_cast<const uint16_t*>(B.ptr) + k0 + kc * 8;
+        if (kleft >= BK) {
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) {
+                const bool isA = i < NCHA;
+                const int row = (isA ? m0 + i * 32 : n0 + (i - NCHA) * 32) + r0;
+                const int rc = min(row, (isA ? A.rows : B.rows) - 1);  // rows past the end: any valid row
+                const uint16_t* g = (isA ? pa : pb) + (int64_t)rc * (isA ? A.ld : B.ld);
+                __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(g), LOQT_LDS_PTR(stage + i * 4096 + wave * 1024), 16, 0,
+                                                 0);
+            }
+        } else {
+            // K tail: through registers, elements past K zeroed in both operands
+            const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
+#pragma unroll 1
+            for (int i = 0; i < NCH; ++i) {
+                const bool isA = i < NCHA;
+                const int row = (isA ? m0 + i * 32 : n0 + (i - NCHA) * 32) + r0;
+                const int rc = min(row, (isA ? A.rows : B.rows) - 1);
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (nv > 0) {
+                    v = *reinterpret_cast<const uint4*>((isA ? pa : pb) + (int64_t)rc * (isA ? A.ld : B.ld));
+                    uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        if (2 * d >= nv) w[d] = 0;
+                        else if (2 * d + 1 >= nv) w[d] &= 0xffffu;
+                    }
+                }
+                *reinterpret_cast<uint4*>(stage + i * 4096 + tid * 16) = v;
+            }
+        }
+    };
+
+    // ---- fragments: row (lane & 31), logical chunk 2*ks + (lane >> 5)
+    const int frow = lane & 31;
+    const int h = lane >> 5;
+    const int fsw = h ^ swz(frow);
+    const int a_off = (wm * Cfg::WTM + frow) * ROWB;
+    const int b_off = BM * ROWB + (wn * Cfg::WTN + frow) * ROWB;
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto load_frags = [&](const char* stage, int ks, int buf) {
+        const int coff = ((2 * ks) ^ fsw) << 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 32 * ROWB + coff);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 32 * ROWB + coff);
+    };
+    // transposed accumulation: D^T = B_frag A_frag^T, so lane = m, registers = n
+    auto mfmas = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
+    };
+
+    if (kt_begin < kt_end) {
+        stage_tile(kt_begin, smem);
+        __syncthreads();  // waits for the direct loads (vmcnt) and the tail writes (lgkmcnt)
+        load_frags(smem, 0, 0);
+        if (kt_begin + 1 < kt_end) stage_tile(kt_begin + 1, smem + STAGE);
+    }
+    for (int kt = kt_begin; kt < kt_end; ++kt) {
+        char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
+        char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
+        load_frags(cur, 1, 1);
+        mfmas(0);
+        LOQT_SCHED_GROUP();
+        load_frags(cur, 2, 0);
+        mfmas(1);
+        LOQT_SCHED_GROUP();
+        load_frags(cur, 3, 1);
+        mfmas(0);
+        LOQT_SCHED_GROUP();
+        __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
+        load_frags(nxt, 0, 0);   // (harmless stale read after the last tile)
+        if (kt + 2 < kt_end) stage_tile(kt + 2, cur);
+        mfmas(1);
+        LOQT_SCHED_GROUP();
+    }
+    __syncthreads();  // LDS is free for the epilogue
+
+    // ------------------------------------------------------------------ epilogues
+    // accumulator tile (ti, tj): lane holds row m = ti*32 + (lane & 31); register 4*g + j holds
+    // column n = tj*32 + 8*g + 4*(lane >> 5) + j.
+    if (EPI == EPI_BF16) {
+        constexpr int EPITCH = Cfg::EPITCH, WTM = Cfg::WTM, WTN = Cfg::WTN;
+        char* ebuf = smem + wave * (WTM * EPITCH);
+#pragma unroll
+        for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < TN; ++tj)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint2 v = make_uint2(
+                        pack_bf16(p.alpha * acc[ti][tj][4 * g + 0], p.alpha * acc[ti][tj][4 * g + 1]),
+                        pack_bf16(p.alpha * acc[ti][tj][4 * g + 2], p.alpha * acc[ti][tj][4 * g + 3]));
+                    *reinterpret_cast<uint2*>(ebuf + (ti * 32 + frow) * EPITCH + (tj * 32 + 8 * g + 4 * h) * 2) = v;
+                }
+        // the region is private to the wave and LDS operations of one wave complete in order
+        constexpr int CPR = WTN / 8;  // 16-byte chunks per row
+        uint16_t* C = reinterpret_cast<uint16_t*>(p.C);
+#pragma unroll 4
+        for (int it = 0; it < WTM * CPR / 64; ++it) {
+            const int idx = it * 64 + lane, row = idx / CPR, ch = idx % CPR;
+            const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + ch * 8;
+            const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * EPITCH + ch * 16);
+            if (m < p.M) {
+                uint16_t* dst = C + (int64_t)m * p.ldc + n;
+                if (n + 8 <= p.N) {
+                    *reinterpret_cast<uint4*>(dst) = v;
+                } else {
+                    const uint16_t* s = reinterpret_cast<const uint16_t*>(&v);
+                    for (int e = 0; e < 8; ++e)
+                        if (n + e < p.N) dst[e] = s[e];
+                }
+            }
+        }
+    } else if (EPI == EPI_F32_SPLITK) {
+        float* C = reinterpret_cast<float*>(p.C) + (int64_t)blockIdx.y * p.M * p.ldc;
+#pragma unroll
+        for (int ti = 0; ti < TM; ++ti) {
+            const int m = m0 + wm * Cfg::WTM + ti * 32 + frow;
+#pragma unroll
+            for (int tj = 0; tj < TN; ++tj)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * Cfg::WTN + tj * 32 + 8 * g + 4 * h;
+                    if (m < p.M) {
+                        float* dst = C + (int64_t)m * p.ldc + n;
+                        if (n + 4 <= p.N) {
+                            *reinterpret_cast<float4*>(dst) =
+                                make_float4(p.alpha * acc[ti][tj][4 * g + 0], p.alpha * acc[ti][tj][4 * g + 1],
+                                            p.alpha * acc[ti][tj][4 * g + 2], p.alpha * acc[ti][tj][4 * g + 3]);
+                        } else {
+                            for (int j = 0; j < 4; ++j)
+                                if (n + j < p.N) dst[j] = p.alpha * acc[ti][tj][4 * g + j];
+                        }
+                    }
+                }
+        }
+    } else {
+        // merge (M = out, N = in): W_new = fl32(absmax * q[code]) + alpha * acc, requantised per
+        // 64-block along n.  A block of row m is 32 values in this lane and 32 in lane ^ 32.
+        float* lut = reinterpret_cast<float*>(smem);
+        if (tid < 16) lut[tid] = kNf4Levels[tid];
+        __syncthreads();
+        const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
+#pragma unroll
+        for (int ti = 0; ti < TM; ++ti) {
+            const int m = m0 + wm * Cfg::WTM + ti * 32 + frow;
+            const bool mvalid = m < p.M;
+#pragma unroll
+            for (int b = 0; b < TN / 2; ++b) {
+                const int nb = n0 + wn * Cfg::WTN + b * 64;  // first `in` index of the block
+                const bool live = mvalid && nb < p.w_ld;
+                float am_old = 0.f;
+                if (live) am_old = p.w_absmax[m * lda + (nb >> 6)];
+                uint32_t cw[8];
+                float v[32];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {  // q = 4*tt + g: tile tt of the pair, column group g
+                    const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
+                    cw[q] = 0x7777u;
+                    if (live) cw[q] = *reinterpret_cast<const uint16_t*>(p.w_codes + m * ldb + (nq >> 1));
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float wold = am_old * lut[nib4(cw[q], j)];
+                        float val = wold + p.alpha * acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j];
+                        if (nq + j >= p.w_cols) val = 0.f;
+                        v[4 * q + j] = val;
+                    }
+                }
+                float amax = 0.f;
+#pragma unroll
+                for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(v[e]));
+                amax = fmaxf(amax, __shfl_xor(amax, 32));
+                Nf4Thresholds th;
+                th.set(amax);
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
+                    uint32_t word = 0;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        uint32_t code = 7u;
+                        if (amax > 0.f && nq + j < p.w_cols) code = th.encode(v[4 * q + j]);
+                        word |= code << (8 * (j >> 1) + ((j & 1) ? 0 : 4));
+                    }
+                    if (live) *reinterpret_cast<uint16_t*>(p.out_codes + m * ldb + (nq >> 1)) = (uint16_t)word;
+                }
+                if (live && h == 0) p.out_absmax[m * lda + (nb >> 6)] = amax;
+            }
+        }
+    }
+}
+
+template <int BM, int BN, int EPI>
+hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
+    auto kern = nt_gemm_kernel<BM, BN, EPI>;
+    constexpr int smem = NtCfg<BM, BN>::SMEM;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+    dim3 grid((tiles + 7) / 8 * 8, EPI == EPI_F32_SPLITK ? p.splits : 1);
+    hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
+    return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
+    // largest tile that still gives every compute unit a work-group
+    const int64_t z = EPI == EPI_F32_SPLITK ? p.splits : 1;
+    auto tiles = [&](int bm, int bn) { return z * ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+    if (tiles(256, 256) >= 224) return launch_nt<256, 256, EPI>(p, st);
+    if (tiles(256, 128) >= 224) return launch_nt<256, 128, EPI>(p, st);
+    return launch_nt<128, 128, EPI>(p, st);
+}
+
+}  // namespace
+
+hipError_t launch_gemm_nt(int slot, int epi, const GemmParams& p, hipStream_t st) {
+    TimedLaunch tl(slot, st);
+    switch (epi) {
+        case EPI_BF16: return launch_nt_sized<EPI_BF16>(p, st);
+        case EPI_F32_SPLITK: return launch_nt_sized<EPI_F32_SPLITK>(p, st);
+        case EPI_MERGE: return launch_nt_sized<EPI_MERGE>(p, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace loqt

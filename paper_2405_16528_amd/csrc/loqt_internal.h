@@ -110,6 +110,7 @@ enum KernelSlot {
     SLOT_GEMM_DB,     // dB partials = Z^T x
     SLOT_REDUCE_DB,   // dB = sum of partials
     SLOT_MERGE,       // fused merge + requantise
+    SLOT_PREPASS,     // NF4 -> bf16 (plain or transposed) and bf16 transposes of the large-token path
     SLOT_COUNT
 };
 
@@ -127,7 +128,8 @@ struct TimedLaunch {
 hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t ld_w, uint8_t* codes,
                            float* absmax, int64_t ld_q, hipStream_t st);
 hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
-                             int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st);
+                             int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st,
+                             int slot = SLOT_DEQUANTIZE);
 
 // operand storage kinds of the GEMM
 enum OpKind {
@@ -168,8 +170,15 @@ struct GemmParams {
 // which GEMM to run
 enum GemmId { GEMM_U = 0, GEMM_Y, GEMM_Z, GEMM_DX, GEMM_DB, GEMM_MERGE };
 hipError_t launch_gemm(GemmId id, const GemmParams& p, hipStream_t st);
-hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, void* dB,
+hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, int64_t ldp, void* dB,
                             int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st);
 int gemm_db_splits(int64_t T, int64_t r, int64_t in);
+
+// large-token path (gemm_nt.hip, prepass.hip): operands bf16, rows x K with K contiguous
+hipError_t launch_gemm_nt(int slot, int epi, const GemmParams& p, hipStream_t st);
+hipError_t launch_dequant_transpose(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
+                                    int64_t ld_q, uint16_t* dst, int64_t ld_d, hipStream_t st);
+hipError_t launch_transpose_bf16(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld_s, uint16_t* dst,
+                                 int64_t ld_d, hipStream_t st);
 
 }  // namespace loqt

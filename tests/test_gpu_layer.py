@@ -12,6 +12,15 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2  # max |err| <= TOL * RMS(reference): the bound stated for bf16 outputs and gradients
 
 
+@pytest.fixture(params=["fused", "prepass"], autouse=True)
+def path(request):
+    """Every test runs once per implementation (NF4 expanded inside the GEMM / by a pre-pass)."""
+    from paper_2405_16528_amd import binding as L
+    L.set_path({"fused": L.PATH_FUSED, "prepass": L.PATH_PREPASS}[request.param])
+    yield request.param
+    L.set_path(L.PATH_AUTO)
+
+
 def _setup(T, out, inp, r, seed, sigma_B=1e-3, name="layer"):
     from tests import gpu_util as G
     lay = synth.make_layer(name, "l", out, inp, r, T, seed)
