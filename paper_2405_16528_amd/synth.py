@@ -55,10 +55,20 @@ def rng_for(seed: int, *names) -> np.random.Generator:
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:
-    """float32 -> bfloat16 bit patterns (uint16), round to nearest even."""
-    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
-    r = ((u >> 16) & 1) + np.uint32(0x7FFF)
-    return ((u + r) >> 16).astype(np.uint16)
+    """float32 -> bfloat16 bit patterns (uint16), round to nearest even (finite inputs)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.reshape(-1).view(np.uint32)
+    out = np.empty(u.shape, dtype=np.uint16)
+    step = 1 << 20  # cache-sized pieces: the conversion is several passes over its input
+    for i in range(0, u.size, step):
+        c = u[i:i + step]
+        r = c >> 16
+        r &= 1
+        r += np.uint32(0x7FFF)
+        r += c
+        r >>= 16
+        out[i:i + step] = r
+    return out.reshape(x.shape)
 
 
 def normal_f32(rng: np.random.Generator, shape, sigma: float) -> np.ndarray:

@@ -1,0 +1,89 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2405_16528_amd", "libloqt.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2405_16528_amd import build
+        build.build(verbose=False)
+    from paper_2405_16528_amd import binding
+    return binding.lib
+
+
+def test_every_declared_symbol_is_exported(lib):
+    hdr = open(os.path.join(ROOT, "include", "loqt.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(nf4_\w+|loqt_\w+)\s*\(", hdr))
+    assert {"nf4_quantize", "nf4_dequantize", "loqt_linear_fwd", "loqt_linear_bwd", "loqt_merge_requant",
+            "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path"} <= names
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
+
+
+def test_status_strings(lib):
+    assert lib.loqt_status_string(0) == b"LOQT_OK"
+    assert lib.loqt_status_string(4) == b"LOQT_WORKSPACE_TOO_SMALL"
+    assert lib.loqt_status_string(99) == b"LOQT_UNKNOWN_STATUS"
+
+
+def test_workspace_sizes(lib):
+    from paper_2405_16528_amd import binding as L
+    T, out, inp, r = 8192, 4096, 4096, 1024
+    fwd = L.loqt_workspace_bytes(L.OP_FWD, T, out, inp, r)
+    bwd = L.loqt_workspace_bytes(L.OP_BWD, T, out, inp, r)
+    mrg = L.loqt_workspace_bytes(L.OP_MERGE, 0, out, inp, r)
+    assert fwd >= T * r * 2 + out * inp * 2 + out * r * 2
+    assert bwd >= 2 * T * r * 2 + inp * out * 2 + r * out * 2 + inp * r * 2 + inp * T * 2
+    assert mrg >= out * r * 2 + inp * r * 2
+    assert fwd % 256 == 0 and bwd % 256 == 0 and mrg % 256 == 0
+    assert L.loqt_workspace_bytes(L.OP_FWD, 0, out, inp, r) == 0
+    assert L.loqt_workspace_bytes(7, T, out, inp, r) == 0
+
+
+def test_bad_arguments_are_rejected_before_launch(lib):
+    """Every call below must fail in the host-side checks (fake but aligned 'device' addresses
+    are never dereferenced there), so this runs without a GPU."""
+    from paper_2405_16528_amd import binding as L
+    P = 0x10000  # aligned, never touched
+    st = lib.nf4_quantize(None, 4, 64, 64, P, P, 64, None)
+    assert st == 1
+    assert lib.nf4_quantize(P, 4, 64, 64, P, P, 96, None) == 2      # ld_q not a multiple of 64
+    assert lib.nf4_quantize(P, 4, 100, 64, P, P, 128, None) == 2     # ld_w < cols
+    assert lib.nf4_quantize(P, 0, 64, 64, P, P, 64, None) == 2       # empty
+    assert lib.nf4_quantize(P + 4, 4, 64, 64, P, P, 64, None) == 3   # misaligned w
+    assert lib.nf4_quantize(P, -1, 64, 64, P, P, 64, None) == 1
+    assert lib.nf4_dequantize(P, P, 4, 64, 64, P, 5, 64, None) == 1  # unknown dtype
+    assert lib.nf4_dequantize(P, P, 4, 64, 64, P, L.BF16, 36, None) == 2  # bf16 pitch not multiple of 8
+
+    W = L.NF4MatC(P, P, 512, 512, 512)
+    Pm = L.NF4MatC(P, P, 512, 128, 128)
+    Pbad = L.NF4MatC(P, P, 256, 128, 128)  # rows differ from W
+    ws = 1 << 30
+    ok_args = dict(x=P, ld_x=512, T=256)
+    assert lib.loqt_linear_fwd(P, 512, 256, C.byref(W), C.byref(Pbad), P, 512, 1.0, P, 512, P, ws, None) == 2
+    assert lib.loqt_linear_fwd(P, 512, 256, C.byref(W), C.byref(Pm), P, 516, 1.0, P, 512, P, ws, None) == 2
+    assert lib.loqt_linear_fwd(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, None, ws, None) == 1
+    assert lib.loqt_linear_fwd(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 16, None) == 4
+    assert lib.loqt_linear_fwd(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P + 16, ws, None) == 3
+    assert lib.loqt_linear_fwd(P, 512, 256, None, C.byref(Pm), P, 512, 1.0, P, 512, P, ws, None) == 1
+    assert lib.loqt_linear_bwd(P, 512, P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, None, 0, 512, 0,
+                               P, ws, None) == 1                                       # dB missing
+    assert lib.loqt_linear_bwd(P, 512, P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 3, 512, 0,
+                               P, ws, None) == 1                                       # unknown dB dtype
+    assert lib.loqt_linear_bwd(P, 512, P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 0, 100, 0,
+                               P, ws, None) == 2                                       # ld_dB < in
+    assert lib.loqt_merge_requant(C.byref(W), None, P, C.byref(Pm), P, 512, 1.0, P, ws, None) == 1
+    assert lib.loqt_merge_requant(C.byref(W), P + 64, P, C.byref(Pm), P, 512, 1.0, P, ws, None) == 1  # partial overlap
+    assert lib.loqt_merge_requant_batched(-1, None, P, ws, None) == 1
+    assert lib.loqt_merge_requant_batched(0, None, P, ws, None) == 0                   # nothing to do
+    assert lib.loqt_set_path(9) == 1
+    assert lib.loqt_set_path(L.PATH_AUTO) == 0
