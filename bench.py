@@ -25,6 +25,10 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 
 METRIC = "LoQT NF4 linear fwd+bwd TFLOP/s at 7B shapes; merge+requant GB/s"
 
+# HBM-side traffic of the dominant kernel per launch, from profiles/bench_7b_block_hbm_traffic.md
+# (fetch 873.0 MB + write 94.2 MB); null for workloads that were not profiled.
+TRAFFIC_BYTES_PER_LAUNCH = {"7b_block": 967.2e6}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -34,25 +38,32 @@ def parse():
     ap.add_argument("--workload", default="7b_block")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=1024)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain device copy of 1 GiB (reference dispatch for HBM byte counters)")
     return ap.parse_args()
 
 
 def cpu_baseline(wl, seed, sample_T):
     """The oracle as it stands, timed on the host cores on a bounded sample of the workload:
-    forward + backward of the first projection on `sample_T` tokens (each output row depends
-    only on its own token, so a token subset is the same arithmetic per token)."""
-    import numpy as np
+    forward + backward of up to three projections (first, gate-like, down-like) on `sample_T`
+    tokens (each output row depends only on its own token, so a token subset is the same
+    arithmetic per token)."""
     from oracle import loqt_oracle as O
     from paper_2405_16528_amd import synth
-    name, out, inp = wl.projections[0]
-    lay = synth.make_layer(wl.name, name, out, inp, wl.r, sample_T, seed)
-    Wq, Pq = O.nf4_quantize(lay.W), O.nf4_quantize(lay.P)
-    t0 = time.perf_counter()
-    O.loqt_linear_fwd(lay.x, Wq, Pq, lay.B, 1.0)
-    O.loqt_linear_bwd(lay.dy, lay.x, Wq, Pq, lay.B, 1.0)
-    dt = time.perf_counter() - t0
-    flops = synth.flops_fwd(sample_T, out, inp, wl.r) + synth.flops_bwd(sample_T, out, inp, wl.r)
+    picks = sorted({0, min(4, len(wl.projections) - 1), len(wl.projections) - 1})
+    secs, flops, names = 0.0, 0, []
+    for pi in picks:
+        name, out, inp = wl.projections[pi]
+        lay = synth.make_layer(wl.name, name, out, inp, wl.r, sample_T, seed)
+        Wq, Pq = O.nf4_quantize(lay.W), O.nf4_quantize(lay.P)
+        t0 = time.perf_counter()
+        O.loqt_linear_fwd(lay.x, Wq, Pq, lay.B, 1.0)
+        O.loqt_linear_bwd(lay.dy, lay.x, Wq, Pq, lay.B, 1.0)
+        secs += time.perf_counter() - t0
+        flops += synth.flops_fwd(sample_T, out, inp, wl.r) + synth.flops_bwd(sample_T, out, inp, wl.r)
+        names.append(f"{name}:{out}x{inp}")
+        del lay, Wq, Pq
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -60,10 +71,10 @@ def cpu_baseline(wl, seed, sample_T):
     env = os.environ.get("OMP_NUM_THREADS")
     if env:
         cores = min(cores, int(env))
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"fwd+bwd of projection '{name}' ({out}x{inp}, r={wl.r}) of {wl.name} on {sample_T} of "
-                      f"{wl.T} tokens, numpy float64, {dt:.2f} s",
-            "seconds": dt}
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"fwd+bwd of projections {', '.join(names)} (r={wl.r}) of {wl.name} on {sample_T} of "
+                      f"{wl.T} tokens, numpy float64, {secs:.1f} s of oracle time",
+            "seconds": secs}
 
 
 def main():
@@ -138,6 +149,12 @@ def main():
             e2.record()
             phase_events.append((e0, e1, e2))
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -174,15 +191,20 @@ def main():
         if name in kflops:
             ent["tflops"] = kflops[name] * args.steps / (ms * 1e-3) / 1e12
         kernels[name] = ent
-    dom = max((k for k in kernels if k in kflops and k != "merge_requant"), key=lambda k: kernels[k]["ms_per_step"])
-    dk = kernels[dom]
-    n_launch = dk["launches_per_step"]
+    # dominant kernel: the 256x256 bf16-epilogue instantiation serves both gemm_y and gemm_dx
+    dom_slots = [k for k in ("gemm_y", "gemm_dx") if k in kernels]
+    dom_ms = sum(kernels[k]["ms_per_step"] for k in dom_slots)
+    dom_launches = sum(kernels[k]["launches_per_step"] for k in dom_slots)
+    dom_flops = sum(kflops[k] for k in dom_slots)
+    dom_tflops = dom_flops / (dom_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": dom, "bound": "mfma",
-        "achieved": dk["tflops"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-        "frac": dk["tflops"] / PEAK_BF16_TFLOPS,
-        "flops_per_launch": kflops[dom] / n_launch, "avg_launch_ms": dk["avg_ms"],
-        "traffic": None,
+        "kernel": "nt_gemm_kernel<256,256,EPI_BF16> (gemm_y + gemm_dx launches)", "bound": "mfma",
+        "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+        "frac": dom_tflops / PEAK_BF16_TFLOPS,
+        "flops_per_launch": dom_flops / dom_launches, "avg_launch_ms": dom_ms / dom_launches,
+        # HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE, rocprofv3 --pmc, scaled by a plain copy):
+        # see profiles/bench_7b_block_hbm_traffic.md; not measurable from inside this process
+        "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(wl.name),
     }
     # the merge is bound by max(HBM stream, rank-r bf16 product); report both views
     mk = kernels.get("merge_requant")
