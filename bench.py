@@ -174,16 +174,24 @@ def main():
     ms_fb = sum(a.elapsed_time(b) for (a, b, _) in phase_events) / args.steps
     ms_mg = sum(b.elapsed_time(c) for (_, b, c) in phase_events) / args.steps
 
-    # algorithmic flops of each GEMM kernel over one step (factored form)
+    # flops each kernel actually executes over one step (depends on the implementation the library picks)
+    folded = {n: L.resolved_path(L.OP_FWD, T, o, i) == L.PATH_FOLDED for (n, o, i) in wl.projections}
     kflops = {
-        "gemm_u": sum(2 * T * i * r for (_, o, i) in wl.projections),
-        "gemm_y": sum(2 * T * o * (i + r) for (_, o, i) in wl.projections),
-        "gemm_z": sum(2 * T * o * r for (_, o, i) in wl.projections),
-        "gemm_dx": sum(2 * T * i * (o + r) for (_, o, i) in wl.projections),
-        "gemm_db": sum(2 * T * r * i for (_, o, i) in wl.projections),
+        "gemm_u": sum(2 * T * i * r for (n, o, i) in wl.projections if not folded[n]),
+        "gemm_y": sum(2 * T * o * (i + (0 if folded[n] else r)) for (n, o, i) in wl.projections),
+        # folded: Z may ride along with dx ([dx | Z] = dy [W_eff | s deq(P)]); its flops are then in gemm_dx
+        "gemm_z+dx": sum(2 * T * o * (i + r) if folded[n] else 2 * T * (o * r + i * (o + r))
+                         for (n, o, i) in wl.projections),
+        "gemm_db": sum(2 * T * r * i for (n, o, i) in wl.projections),
+        "fold_weight": sum(2 * 2 * o * i * r for (n, o, i) in wl.projections if folded[n]),
         "merge_requant": f_mg,
     }
+    f_exec = sum(v for k, v in kflops.items() if k != "merge_requant")
     kernels = {}
+    if "gemm_z" in kt or "gemm_dx" in kt:
+        nz, mz = kt.pop("gemm_z", (0, 0.0))
+        nd, md = kt.pop("gemm_dx", (0, 0.0))
+        kt["gemm_z+dx"] = (nz + nd, mz + md)
     for name, (n, ms) in kt.items():
         if n == 0:
             continue
@@ -192,13 +200,13 @@ def main():
             ent["tflops"] = kflops[name] * args.steps / (ms * 1e-3) / 1e12
         kernels[name] = ent
     # dominant kernel: the 256x256 bf16-epilogue instantiation serves both gemm_y and gemm_dx
-    dom_slots = [k for k in ("gemm_y", "gemm_dx") if k in kernels]
+    dom_slots = [k for k in ("gemm_y", "gemm_z+dx") if k in kernels]
     dom_ms = sum(kernels[k]["ms_per_step"] for k in dom_slots)
     dom_launches = sum(kernels[k]["launches_per_step"] for k in dom_slots)
     dom_flops = sum(kflops[k] for k in dom_slots)
     dom_tflops = dom_flops / (dom_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "nt_gemm_kernel<256,256,EPI_BF16> (gemm_y + gemm_dx launches)", "bound": "mfma",
+        "kernel": "nt_gemm_kernel<*,*,EPI_BF16> (gemm_y, gemm_dx and gemm_z launches)", "bound": "mfma",
         "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": dom_tflops / PEAK_BF16_TFLOPS,
         "flops_per_launch": dom_flops / dom_launches, "avg_launch_ms": dom_ms / dom_launches,
@@ -228,6 +236,10 @@ def main():
                    "projections": [f"{n}:{o}x{i}" for (n, o, i) in wl.projections],
                    "step": "7x(loqt_linear_fwd + loqt_linear_bwd) + batched merge/requant of the block"},
         "fwd_bwd": {"tflops": f_fb / (ms_fb * 1e-3) / 1e12, "ms_per_step": ms_fb,
+                    "flop_model": "algorithmic, factored form: fwd 2T(out*in + in*r + r*out), bwd 2T(out*in + out*r + 2*r*in)",
+                    "executed_tflops": f_exec / (ms_fb * 1e-3) / 1e12,
+                    "paths": sorted({["auto", "fused", "prepass", "folded"][L.resolved_path(L.OP_FWD, T, o, i)]
+                                     for (_, o, i) in wl.projections}),
                     "frac_of_bf16_peak": f_fb / (ms_fb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         "merge": merge,
         "kernels": kernels,

@@ -175,12 +175,21 @@ loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *desc
  *   LOQT_PATH_PREPASS: NF4 operands are expanded to bf16 in the workspace by one streaming pass
  *                      per call (transposed where the product needs it), then every product is
  *                      a K-contiguous bf16 GEMM fed by direct global->LDS loads.
- *   LOQT_PATH_AUTO   : pre-pass when at least 1024 rows (tokens; `in` for the merge) share each
- *                      weight tile, fused below that.
- * Both compute the same quantities; results differ only in fp32 summation order.
+ *   LOQT_PATH_FOLDED : as PREPASS, but forward and backward first fold the rank-r term into the
+ *                      bf16 copy of the weight, W_eff = deq(W_q) + s deq(P_q) B (a rank-r product of
+ *                      2 out in r flop with fp32 accumulation), and then run single products
+ *                      y = x W_eff^T and dx = dy W_eff.  The intermediate U is not formed; Z still is
+ *                      (dB = Z^T x).  Cheaper than carrying the rank-r term through every token
+ *                      (2 T r (in + out) flop per pass) from T = out in / (in + out) tokens up.
+ *   LOQT_PATH_AUTO   : fused below 1024 rows (tokens; `in` for the merge) per weight tile, else
+ *                      pre-pass; folded when T (in + out) >= 2 out in.
+ * All compute the same quantities; results differ only in rounding order, within the stated
+ * tolerance.
  */
-enum { LOQT_PATH_AUTO = 0, LOQT_PATH_FUSED = 1, LOQT_PATH_PREPASS = 2 };
+enum { LOQT_PATH_AUTO = 0, LOQT_PATH_FUSED = 1, LOQT_PATH_PREPASS = 2, LOQT_PATH_FOLDED = 3 };
 loqt_status loqt_set_path(int path);
+/* The implementation (FUSED, PREPASS or FOLDED) the current option selects for these sizes. */
+int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in);
 
 /*
  * Optional per-kernel timing (diagnostics for benchmarks; off by default).

@@ -23,7 +23,7 @@ lib = C.CDLL(_LIB_PATH)
 
 F32, BF16 = 0, 1
 OP_FWD, OP_BWD, OP_MERGE = 0, 1, 2
-PATH_AUTO, PATH_FUSED, PATH_PREPASS = 0, 1, 2
+PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
                 4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
 
@@ -66,6 +66,8 @@ lib.loqt_merge_requant_batched.restype = _i
 lib.loqt_merge_requant_batched.argtypes = [_i, _P(MergeDescC), _vp, _sz, _vp]
 lib.loqt_set_path.restype = _i
 lib.loqt_set_path.argtypes = [_i]
+lib.loqt_resolved_path.restype = _i
+lib.loqt_resolved_path.argtypes = [_i, _i64, _i64, _i64]
 lib.loqt_timing_enable.restype = None
 lib.loqt_timing_enable.argtypes = [_i]
 lib.loqt_timing_slots.restype = _i
@@ -196,6 +198,10 @@ def loqt_merge_requant_batched(descs, ws: Optional[torch.Tensor] = None) -> None
 def set_path(path: int) -> None:
     """PATH_AUTO, PATH_FUSED or PATH_PREPASS (process-wide)."""
     _check(lib.loqt_set_path(path), "loqt_set_path")
+
+
+def resolved_path(op: int, T: int, out: int, inp: int) -> int:
+    return int(lib.loqt_resolved_path(op, T, out, inp))
 
 
 def timing_enable(on: bool) -> None:

@@ -1,6 +1,8 @@
 // C ABI of libloqt: argument checking, workspace layout, launch sequences, timing.
 #include <string.h>
 
+#include <algorithm>
+
 #include "loqt_internal.h"
 
 namespace loqt {
@@ -18,7 +20,7 @@ struct TimingState {
     int created = 0;
 } g_timing;
 const char* kSlotNames[SLOT_COUNT] = {"nf4_quantize", "nf4_dequantize", "gemm_u",   "gemm_y",      "gemm_z",
-                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant", "prepass"};
+                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant", "prepass", "fold_weight"};
 }  // namespace
 
 TimedLaunch::TimedLaunch(int slot_, hipStream_t s) : stream(s), slot(slot_), idx(-1) {
@@ -89,8 +91,17 @@ int g_path = LOQT_PATH_AUTO;
 
 bool use_prepass(int64_t rows_sharing_weights) {
     if (g_path == LOQT_PATH_FUSED) return false;
-    if (g_path == LOQT_PATH_PREPASS) return true;
+    if (g_path == LOQT_PATH_PREPASS || g_path == LOQT_PATH_FOLDED) return true;
     return rows_sharing_weights >= 1024;
+}
+
+// Within the pre-pass family: carry the rank-r term through every token as a second K segment
+// (2 T r (in + out) flop per pass) or fold it into the bf16 copy of the weight once per call
+// (W_eff = deq(W) + s deq(P) B, 2 out in r flop).  Folding wins from T = out in / (in + out) up.
+bool use_folded(int64_t T, int64_t out, int64_t in) {
+    if (g_path == LOQT_PATH_FOLDED) return true;
+    if (g_path != LOQT_PATH_AUTO) return false;
+    return T * (in + out) >= 2 * out * in;
 }
 
 inline size_t bf16_bytes(int64_t rows, int64_t cols) {
@@ -101,16 +112,17 @@ size_t bwd_z_bytes(int64_t T, int64_t r) { return bf16_bytes(T, r); }
 // index arithmetic of the NT kernel: 32-bit row offsets are not used, but rows * pitch must
 // stay below 2^40 elements; the host checks shapes against kMaxDim only.
 struct FwdWs {  // prepass forward
-    size_t U, Wb, Pb, total;
+    size_t U, Wb, Pb, Bt, total;
     FwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
         U = 0;
         Wb = U + bf16_bytes(T, r);
         Pb = Wb + bf16_bytes(out, in);
-        total = Pb + bf16_bytes(out, r);
+        Bt = Pb + bf16_bytes(out, r);
+        total = Bt + bf16_bytes(in, r);
     }
 };
 struct BwdWs {  // prepass backward
-    size_t Z, Zt, Wt, Pt, Bt, xt, partials, total;
+    size_t Z, Zt, Wt, Pt, Bt, xt, Pb, We, partials, total;
     int splits;
     int64_t ldp;
     BwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
@@ -120,15 +132,25 @@ struct BwdWs {  // prepass backward
         Wt = Pt + bf16_bytes(r, out);
         Bt = Wt + bf16_bytes(in, out);
         xt = Bt + bf16_bytes(in, r);
-        partials = xt + bf16_bytes(in, T);
+        Pb = xt + bf16_bytes(in, T);
+        We = Pb + bf16_bytes(out, r);
+        partials = We + bf16_bytes(out, in);
         ldp = (int64_t)round_up(in, 4);
-        // split the contraction over T until the grid fills the machine twice over
+        // split the contraction over T: the fewest slices whose work-group count fills whole
+        // rounds of the 256 compute units to at least 90 % (each slice at least 512 deep)
         const int64_t tiles = ((r + 255) / 256) * ((in + 255) / 256);
-        int64_t s = (512 + tiles - 1) / tiles;
-        const int64_t max_s = (T + 511) / 512;
-        if (s > max_s) s = max_s;
-        if (s < 1) s = 1;
-        if (s > 16) s = 16;
+        const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, T / 512));
+        int64_t s = 1;
+        double best = 0.0;
+        for (int64_t c = 1; c <= max_s; ++c) {
+            const int64_t w = tiles * c;
+            const double eff = (double)w / (double)(((w + 255) / 256) * 256);
+            if (eff > best + 1e-9) {
+                best = eff;
+                s = c;
+            }
+            if (eff >= 0.9) break;
+        }
         splits = (int)s;
         total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
     }
@@ -164,6 +186,30 @@ Operand no_operand() {
     Operand o;
     memset(&o, 0, sizeof(o));
     return o;
+}
+
+// W_eff[out x in] (bf16, pitch ldw) = deq(Wq) + s * deq(Pq) B; Pb and Bt are scratch
+loqt_status fold_weight(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
+                        uint16_t* Pb, uint16_t* Bt, uint16_t* We, int64_t ldw, hipStream_t st) {
+    const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
+    const int64_t ldr = (int64_t)round_up(r, 8);
+    LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ldr, st, SLOT_PREPASS));
+    LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ldr, st));
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(Pb, ldr, (int)out, (int)r);
+    p.B[0] = bf16_operand(Bt, ldr, (int)in, (int)r);
+    p.M = (int)out;
+    p.N = (int)in;
+    p.alpha = s;
+    p.C = We;
+    p.ldc = ldw;
+    p.w_codes = Wq->codes;
+    p.w_absmax = Wq->absmax;
+    p.w_ld = Wq->ld;
+    p.w_cols = (int)in;
+    LOQT_HIP(launch_gemm_nt(SLOT_FOLD, EPI_FOLD, p, st));
+    return LOQT_OK;
 }
 
 loqt_status merge_fused(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
@@ -332,6 +378,20 @@ loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
         uint16_t* Wb = reinterpret_cast<uint16_t*>(base + L.Wb);
         uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
         const int64_t ldw = (int64_t)round_up(in, 8);
+        if (use_folded(T, out, in)) {
+            // y = x W_eff^T with W_eff = deq(W) + s deq(P) B folded once per call
+            LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, reinterpret_cast<uint16_t*>(base + L.Bt), Wb, ldw, st));
+            memset(&p, 0, sizeof(p));
+            p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+            p.B[0] = bf16_operand(Wb, ldw, (int)out, (int)in);
+            p.M = (int)T;
+            p.N = (int)out;
+            p.alpha = 1.0f;
+            p.C = y;
+            p.ldc = ld_y;
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, p, st));
+            return LOQT_OK;
+        }
         LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wb, LOQT_BF16, ldw, st, SLOT_PREPASS));
         LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_u, st, SLOT_PREPASS));
         // U = s x B^T
@@ -418,16 +478,50 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
         const int64_t ldo = (int64_t)round_up(out, 8), ldT = (int64_t)round_up(T, 8);
         // Z = s dy deq(P): B operand is deq(P)^T, r x out
         LOQT_HIP(launch_dequant_transpose(Pq->codes, Pq->absmax, out, r, Pq->ld, Pt, ldo, st));
-        memset(&p, 0, sizeof(p));
-        p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
-        p.B[0] = bf16_operand(Pt, ldo, (int)r, (int)out);
-        p.M = (int)T;
-        p.N = (int)r;
-        p.alpha = s;
-        p.C = Z;
-        p.ldc = ld_z;
-        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, p, st));
-        if (dx) {
+        const bool folded = dx && use_folded(T, out, in);
+        // Z rides along with dx (one product [dx | Z] over the shared operand dy) when its tiles fit
+        // into the last, partly empty round of 256x256 tiles of the dx product; otherwise its own launch
+        bool z_with_dx = false;
+        if (folded) {
+            const int64_t tm = (T + 255) / 256;
+            const int64_t t_dx = tm * ((in + 255) / 256), t_both = t_dx + tm * ((r + 255) / 256);
+            z_with_dx = t_dx >= 224 && (t_both + 255) / 256 == (t_dx + 255) / 256;
+        }
+        if (!z_with_dx) {
+            memset(&p, 0, sizeof(p));
+            p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+            p.B[0] = bf16_operand(Pt, ldo, (int)r, (int)out);
+            p.M = (int)T;
+            p.N = (int)r;
+            p.alpha = s;
+            p.C = Z;
+            p.ldc = ld_z;
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, p, st));
+        }
+        if (folded) {
+            // [dx | Z] = dy [W_eff | s deq(P)]: one product over the shared operand dy; W_eff is
+            // folded first and transposed to in x out for the K-contiguous form
+            uint16_t* We = reinterpret_cast<uint16_t*>(base + L.We);
+            const int64_t ldw = (int64_t)round_up(in, 8);
+            LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, reinterpret_cast<uint16_t*>(base + L.Pb), Bt, We, ldw, st));
+            LOQT_HIP(launch_transpose_bf16(We, out, in, ldw, Wt, ldo, st));
+            memset(&p, 0, sizeof(p));
+            p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+            p.B[0] = bf16_operand(Wt, ldo, (int)in, (int)out);
+            p.M = (int)T;
+            p.N = (int)in;
+            p.alpha = 1.0f;
+            p.C = dx;
+            p.ldc = ld_dx;
+            if (z_with_dx) {
+                p.Bx = bf16_operand(Pt, ldo, (int)r, (int)out);
+                p.Nx = (int)r;
+                p.alphax = s;
+                p.Cx = Z;
+                p.ldcx = ld_z;
+            }
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, p, st));
+        } else if (dx) {
             // dx = dy deq(W) + Z B: B operands are deq(W)^T (in x out) and B^T (in x r)
             LOQT_HIP(launch_dequant_transpose(Wq->codes, Wq->absmax, out, in, Wq->ld, Wt, ldo, st));
             LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ld_z, st));
@@ -520,8 +614,14 @@ loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc* desc
     return LOQT_OK;
 }
 
+int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in) {
+    if (op == LOQT_OP_MERGE) return use_prepass(in) ? LOQT_PATH_PREPASS : LOQT_PATH_FUSED;
+    if (!use_prepass(T)) return LOQT_PATH_FUSED;
+    return use_folded(T, out, in) ? LOQT_PATH_FOLDED : LOQT_PATH_PREPASS;
+}
+
 loqt_status loqt_set_path(int path) {
-    if (path != LOQT_PATH_AUTO && path != LOQT_PATH_FUSED && path != LOQT_PATH_PREPASS) return LOQT_INVALID_ARG;
+    if (path < LOQT_PATH_AUTO || path > LOQT_PATH_FOLDED) return LOQT_INVALID_ARG;
     g_path = path;
     return LOQT_OK;
 }

@@ -73,7 +73,8 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     const int wm = wave >> 1, wn = wave & 1;
 
     // ---- tile of this work-group: contiguous range per XCD, 8-row groups inside
-    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const int tiles_m = (p.M + BM - 1) / BM;
+    const int tiles_n0 = (p.N + BN - 1) / BN, tiles_n = tiles_n0 + (p.Nx + BN - 1) / BN;
     const int per_xcd = gridDim.x >> 3;
     const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (L >= tiles_m * tiles_n) return;
@@ -82,8 +83,13 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     const int first_m = gid * GM;
     const int gsz = min(tiles_m - first_m, GM);
     const int rem = L - gid * GM * tiles_n;
-    const int tm = first_m + rem % gsz, tn = rem / gsz;
+    const int tm = first_m + rem % gsz;
+    int tn = rem / gsz;
+    const bool part1 = tn >= tiles_n0;  // second column range
+    if (part1) tn -= tiles_n0;
     const int m0 = tm * BM, n0 = tn * BN;
+    const int N = part1 ? p.Nx : p.N;
+    const float alpha = part1 ? p.alphax : p.alpha;
 
     const int nkt0 = (p.A[0].K + BK - 1) / BK;
     const int nkt1 = (p.A[1].K + BK - 1) / BK;
@@ -111,7 +117,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         const int seg = kt >= nkt0 ? 1 : 0;
         const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
         const Operand& A = p.A[seg];
-        const Operand& B = p.B[seg];
+        const Operand& B = part1 ? p.Bx : p.B[seg];
         const int kleft = A.K - k0;
         const uint16_t* pa = reinterpret_cast<const uint16_t*>(A.ptr) + k0 + kc * 8;
         const uint16_t* pb = reinterpret_cast<const uint16_t*>(B.ptr) + k0 + kc * 8;
@@ -202,36 +208,64 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     // ------------------------------------------------------------------ epilogues
     // accumulator tile (ti, tj): lane holds row m = ti*32 + (lane & 31); register 4*g + j holds
     // column n = tj*32 + 8*g + 4*(lane >> 5) + j.
-    if (EPI == EPI_BF16) {
+    if (EPI == EPI_BF16 || EPI == EPI_FOLD) {
         constexpr int EPITCH = Cfg::EPITCH, WTM = Cfg::WTM, WTN = Cfg::WTN;
+        float* lut = reinterpret_cast<float*>(smem + Cfg::SMEM - 64);
+        if (EPI == EPI_FOLD) {
+            if (tid < 16) lut[tid] = kNf4Levels[tid];
+            __syncthreads();
+        }
         char* ebuf = smem + wave * (WTM * EPITCH);
+        const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
 #pragma unroll
         for (int ti = 0; ti < TM; ++ti)
 #pragma unroll
-            for (int tj = 0; tj < TN; ++tj)
+            for (int tj = 0; tj < TN; ++tj) {
+                // folded weight (M = out, N = in): the 16 code bytes of row m, columns nt..nt+31 (both
+                // lanes of a pair load them; this lane uses the half-words (lane >> 5) of each dword)
+                uint32_t cw4[4] = {0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};
+                float am = 0.f;
+                if (EPI == EPI_FOLD) {
+                    const int m = m0 + wm * WTM + ti * 32 + frow;
+                    const int nt = n0 + wn * WTN + tj * 32;
+                    if (m < p.M && nt < p.w_ld) {
+                        const uint4 c = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nt >> 1));
+                        cw4[0] = c.x, cw4[1] = c.y, cw4[2] = c.z, cw4[3] = c.w;
+                        am = p.w_absmax[m * lda + (nt >> 6)];
+                    }
+                }
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const uint2 v = make_uint2(
-                        pack_bf16(p.alpha * acc[ti][tj][4 * g + 0], p.alpha * acc[ti][tj][4 * g + 1]),
-                        pack_bf16(p.alpha * acc[ti][tj][4 * g + 2], p.alpha * acc[ti][tj][4 * g + 3]));
+                    float v0 = alpha * acc[ti][tj][4 * g + 0], v1 = alpha * acc[ti][tj][4 * g + 1];
+                    float v2 = alpha * acc[ti][tj][4 * g + 2], v3 = alpha * acc[ti][tj][4 * g + 3];
+                    if (EPI == EPI_FOLD) {
+                        const uint32_t cw = (cw4[g] >> (16 * h)) & 0xffffu;
+                        v0 += am * lut[nib4(cw, 0)];
+                        v1 += am * lut[nib4(cw, 1)];
+                        v2 += am * lut[nib4(cw, 2)];
+                        v3 += am * lut[nib4(cw, 3)];
+                    }
+                    const uint2 v = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
                     *reinterpret_cast<uint2*>(ebuf + (ti * 32 + frow) * EPITCH + (tj * 32 + 8 * g + 4 * h) * 2) = v;
                 }
+            }
         // the region is private to the wave and LDS operations of one wave complete in order
         constexpr int CPR = WTN / 8;  // 16-byte chunks per row
-        uint16_t* C = reinterpret_cast<uint16_t*>(p.C);
+        uint16_t* C = reinterpret_cast<uint16_t*>(part1 ? p.Cx : p.C);
+        const int64_t ldc = part1 ? p.ldcx : p.ldc;
 #pragma unroll 4
         for (int it = 0; it < WTM * CPR / 64; ++it) {
             const int idx = it * 64 + lane, row = idx / CPR, ch = idx % CPR;
             const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + ch * 8;
             const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * EPITCH + ch * 16);
             if (m < p.M) {
-                uint16_t* dst = C + (int64_t)m * p.ldc + n;
-                if (n + 8 <= p.N) {
+                uint16_t* dst = C + (int64_t)m * ldc + n;
+                if (n + 8 <= N) {
                     *reinterpret_cast<uint4*>(dst) = v;
                 } else {
                     const uint16_t* s = reinterpret_cast<const uint16_t*>(&v);
                     for (int e = 0; e < 8; ++e)
-                        if (n + e < p.N) dst[e] = s[e];
+                        if (n + e < N) dst[e] = s[e];
                 }
             }
         }
@@ -275,16 +309,22 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 const bool live = mvalid && nb < p.w_ld;
                 float am_old = 0.f;
                 if (live) am_old = p.w_absmax[m * lda + (nb >> 6)];
-                uint32_t cw[8];
+                // the 2 x 16 code bytes of the block (columns nb..nb+63 of row m); both lanes of a pair
+                // load them, this lane owns the half-words (lane >> 5) of each dword
+                uint4 cw4[2];
+                cw4[0] = cw4[1] = make_uint4(0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u);
+                if (live) {
+                    cw4[0] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1));
+                    cw4[1] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1) + 16);
+                }
                 float v[32];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {  // q = 4*tt + g: tile tt of the pair, column group g
                     const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
-                    cw[q] = 0x7777u;
-                    if (live) cw[q] = *reinterpret_cast<const uint16_t*>(p.w_codes + m * ldb + (nq >> 1));
+                    const uint32_t cw = (reinterpret_cast<const uint32_t*>(&cw4[q >> 2])[q & 3] >> (16 * h)) & 0xffffu;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float wold = am_old * lut[nib4(cw[q], j)];
+                        const float wold = am_old * lut[nib4(cw, j)];
                         float val = wold + p.alpha * acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j];
                         if (nq + j >= p.w_cols) val = 0.f;
                         v[4 * q + j] = val;
@@ -297,16 +337,25 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 Nf4Thresholds th;
                 th.set(amax);
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
-                    uint32_t word = 0;
+                for (int tt = 0; tt < 2; ++tt) {
+                    uint32_t o[4];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        uint32_t code = 7u;
-                        if (amax > 0.f && nq + j < p.w_cols) code = th.encode(v[4 * q + j]);
-                        word |= code << (8 * (j >> 1) + ((j & 1) ? 0 : 4));
+                    for (int g = 0; g < 4; ++g) {
+                        const int q = 4 * tt + g;
+                        const int nq = nb + tt * 32 + 8 * g + 4 * h;
+                        uint32_t word = 0;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            uint32_t code = 7u;
+                            if (amax > 0.f && nq + j < p.w_cols) code = th.encode(v[4 * q + j]);
+                            word |= code << (8 * (j >> 1) + ((j & 1) ? 0 : 4));
+                        }
+                        word <<= 16 * h;                       // this lane's half of dword g
+                        o[g] = word | __shfl_xor(word, 32);    // the partner lane holds the other half
                     }
-                    if (live) *reinterpret_cast<uint16_t*>(p.out_codes + m * ldb + (nq >> 1)) = (uint16_t)word;
+                    if (live && h == 0)
+                        *reinterpret_cast<uint4*>(p.out_codes + m * ldb + (nb >> 1) + tt * 16) =
+                            make_uint4(o[0], o[1], o[2], o[3]);
                 }
                 if (live && h == 0) p.out_absmax[m * lda + (nb >> 6)] = amax;
             }
@@ -325,7 +374,7 @@ hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+    const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN + (p.Nx + BN - 1) / BN);
     dim3 grid((tiles + 7) / 8 * 8, EPI == EPI_F32_SPLITK ? p.splits : 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
     return hipGetLastError();
@@ -335,7 +384,9 @@ template <int EPI>
 hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     // largest tile that still gives every compute unit a work-group
     const int64_t z = EPI == EPI_F32_SPLITK ? p.splits : 1;
-    auto tiles = [&](int bm, int bn) { return z * ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn); };
+    auto tiles = [&](int bm, int bn) {
+        return z * ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn + (p.Nx + bn - 1) / bn);
+    };
     if (tiles(256, 256) >= 224) return launch_nt<256, 256, EPI>(p, st);
     if (tiles(256, 128) >= 224) return launch_nt<256, 128, EPI>(p, st);
     return launch_nt<128, 128, EPI>(p, st);
@@ -349,6 +400,7 @@ hipError_t launch_gemm_nt(int slot, int epi, const GemmParams& p, hipStream_t st
         case EPI_BF16: return launch_nt_sized<EPI_BF16>(p, st);
         case EPI_F32_SPLITK: return launch_nt_sized<EPI_F32_SPLITK>(p, st);
         case EPI_MERGE: return launch_nt_sized<EPI_MERGE>(p, st);
+        case EPI_FOLD: return launch_nt_sized<EPI_FOLD>(p, st);
     }
     return hipErrorInvalidValue;
 }

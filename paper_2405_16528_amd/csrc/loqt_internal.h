@@ -111,6 +111,7 @@ enum KernelSlot {
     SLOT_REDUCE_DB,   // dB = sum of partials
     SLOT_MERGE,       // fused merge + requantise
     SLOT_PREPASS,     // NF4 -> bf16 (plain or transposed) and bf16 transposes of the large-token path
+    SLOT_FOLD,        // W_eff = deq(W) + s deq(P) B in bf16 (folded path)
     SLOT_COUNT
 };
 
@@ -148,7 +149,7 @@ struct Operand {
     int K;                // extent along the contraction
 };
 
-enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2 };
+enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3 };
 
 struct GemmParams {
     Operand A[2], B[2];  // up to two K segments; segment 1 unused when A[1].K == 0
@@ -158,6 +159,13 @@ struct GemmParams {
     void* C;
     int64_t ldc;
     int splits;  // EPI_F32_SPLITK: number of K splits (grid.y)
+    // optional second column range (NT kernel, EPI_BF16, one K segment): columns N..N+Nx-1 of the
+    // product use operand Bx and go to Cx with their own scale; tiles never straddle the ranges
+    Operand Bx;
+    void* Cx;
+    int64_t ldcx;
+    int Nx;
+    float alphax;
     // EPI_MERGE (M = in, N = out): old weight and destination
     const uint8_t* w_codes;
     const float* w_absmax;

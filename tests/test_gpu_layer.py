@@ -12,11 +12,11 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2  # max |err| <= TOL * RMS(reference): the bound stated for bf16 outputs and gradients
 
 
-@pytest.fixture(params=["fused", "prepass"], autouse=True)
+@pytest.fixture(params=["fused", "prepass", "folded"], autouse=True)
 def path(request):
     """Every test runs once per implementation (NF4 expanded inside the GEMM / by a pre-pass)."""
     from paper_2405_16528_amd import binding as L
-    L.set_path({"fused": L.PATH_FUSED, "prepass": L.PATH_PREPASS}[request.param])
+    L.set_path({"fused": L.PATH_FUSED, "prepass": L.PATH_PREPASS, "folded": L.PATH_FOLDED}[request.param])
     yield request.param
     L.set_path(L.PATH_AUTO)
 
