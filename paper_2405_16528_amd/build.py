@@ -8,7 +8,7 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SOURCES = ["api.hip", "codec.hip", "gemm.hip", "gemm_nt.hip", "prepass.hip"]
+SOURCES = ["api.hip", "codec.hip", "gemm.hip", "gemm_nt.hip"]
 LIB = os.path.join(PKG, "libloqt.so")
 
 FLAGS = [

@@ -109,32 +109,27 @@ inline size_t bf16_bytes(int64_t rows, int64_t cols) {
 }
 size_t bwd_z_bytes(int64_t T, int64_t r) { return bf16_bytes(T, r); }
 
-// index arithmetic of the NT kernel: 32-bit row offsets are not used, but rows * pitch must
-// stay below 2^40 elements; the host checks shapes against kMaxDim only.
-struct FwdWs {  // prepass forward
-    size_t U, Wb, Pb, Bt, total;
+// Workspace layouts of the pre-pass family.  Products take their operands in whichever orientation
+// they are stored (rows x K or K x rows), so nothing is ever transposed: the only pre-passes are NF4
+// expansions, one per NF4 operand and call.
+struct FwdWs {
+    size_t U, Wb, Pb, total;  // U = s x B^T; Wb = deq(W) or W_eff; Pb = deq(P)
     FwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
         U = 0;
         Wb = U + bf16_bytes(T, r);
         Pb = Wb + bf16_bytes(out, in);
-        Bt = Pb + bf16_bytes(out, r);
-        total = Bt + bf16_bytes(in, r);
+        total = Pb + bf16_bytes(out, r);
     }
 };
-struct BwdWs {  // prepass backward
-    size_t Z, Zt, Wt, Pt, Bt, xt, Pb, We, partials, total;
+struct BwdWs {
+    size_t Z, Wb, Pb, partials, total;  // Z = s dy deq(P); Wb = deq(W) or W_eff; Pb = deq(P); dB slices
     int splits;
     int64_t ldp;
     BwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
         Z = 0;
-        Zt = Z + bf16_bytes(T, r);
-        Pt = Zt + bf16_bytes(r, T);
-        Wt = Pt + bf16_bytes(r, out);
-        Bt = Wt + bf16_bytes(in, out);
-        xt = Bt + bf16_bytes(in, r);
-        Pb = xt + bf16_bytes(in, T);
-        We = Pb + bf16_bytes(out, r);
-        partials = We + bf16_bytes(out, in);
+        Wb = Z + bf16_bytes(T, r);
+        Pb = Wb + bf16_bytes(out, in);
+        partials = Pb + bf16_bytes(out, r);
         ldp = (int64_t)round_up(in, 4);
         // split the contraction over T: the fewest slices whose work-group count fills whole
         // rounds of the 256 compute units to at least 90 % (each slice at least 512 deep)
@@ -155,12 +150,12 @@ struct BwdWs {  // prepass backward
         total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
     }
 };
-struct MergeWs {  // prepass merge
-    size_t Pb, Bt, total;
+struct MergeWs {
+    size_t Pb, total;
     MergeWs(int64_t out, int64_t in, int64_t r) {
+        (void)in;
         Pb = 0;
-        Bt = Pb + bf16_bytes(out, r);
-        total = Bt + bf16_bytes(in, r);
+        total = Pb + bf16_bytes(out, r);
     }
 };
 
@@ -188,17 +183,17 @@ Operand no_operand() {
     return o;
 }
 
-// W_eff[out x in] (bf16, pitch ldw) = deq(Wq) + s * deq(Pq) B; Pb and Bt are scratch
+// W_eff[out x in] (bf16, pitch ldw) = deq(Wq) + s * deq(Pq) B; Pb receives deq(Pq) in bf16
 loqt_status fold_weight(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
-                        uint16_t* Pb, uint16_t* Bt, uint16_t* We, int64_t ldw, hipStream_t st) {
+                        uint16_t* Pb, uint16_t* We, int64_t ldw, bool dequant_p, hipStream_t st) {
     const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
     const int64_t ldr = (int64_t)round_up(r, 8);
-    LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ldr, st, SLOT_PREPASS));
-    LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ldr, st));
+    if (dequant_p)
+        LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ldr, st, SLOT_PREPASS));
     GemmParams p;
     memset(&p, 0, sizeof(p));
-    p.A[0] = bf16_operand(Pb, ldr, (int)out, (int)r);
-    p.B[0] = bf16_operand(Bt, ldr, (int)in, (int)r);
+    p.A[0] = bf16_operand(Pb, ldr, (int)out, (int)r);   // out x r, K contiguous
+    p.B[0] = bf16_operand(B, ld_B, (int)in, (int)r);    // r x in: K x rows
     p.M = (int)out;
     p.N = (int)in;
     p.alpha = s;
@@ -208,7 +203,7 @@ loqt_status fold_weight(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const lo
     p.w_absmax = Wq->absmax;
     p.w_ld = Wq->ld;
     p.w_cols = (int)in;
-    LOQT_HIP(launch_gemm_nt(SLOT_FOLD, EPI_FOLD, p, st));
+    LOQT_HIP(launch_gemm_nt(SLOT_FOLD, EPI_FOLD, false, true, p, st));
     return LOQT_OK;
 }
 
@@ -239,18 +234,15 @@ loqt_status merge_prepass(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* abs
                           hipStream_t st) {
     const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
     const MergeWs L(out, in, r);
-    char* base = reinterpret_cast<char*>(ws);
-    uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
-    uint16_t* Bt = reinterpret_cast<uint16_t*>(base + L.Bt);
+    uint16_t* Pb = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(ws) + L.Pb);
     const int64_t ldr = (int64_t)round_up(r, 8);
     LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ldr, st, SLOT_PREPASS));
-    LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ldr, st));
     GemmParams p;
     memset(&p, 0, sizeof(p));
     p.A[0] = bf16_operand(Pb, ldr, (int)out, (int)r);  // rows of the tile are rows of W
-    p.B[0] = bf16_operand(Bt, ldr, (int)in, (int)r);   // columns run along `in`
+    p.B[0] = bf16_operand(B, ld_B, (int)in, (int)r);   // r x in: K x rows, columns run along `in`
     p.M = (int)out;
-    p.N = (int)Wq->ld;  // reach the padding columns (operand rows past `in` are never used)
+    p.N = (int)Wq->ld;  // reach the padding columns (operand columns past `in` are never used)
     p.alpha = s;
     p.w_codes = Wq->codes;
     p.w_absmax = Wq->absmax;
@@ -258,7 +250,7 @@ loqt_status merge_prepass(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* abs
     p.out_absmax = absmax_out;
     p.w_ld = Wq->ld;
     p.w_cols = (int)in;
-    LOQT_HIP(launch_gemm_nt(SLOT_MERGE, EPI_MERGE, p, st));
+    LOQT_HIP(launch_gemm_nt(SLOT_MERGE, EPI_MERGE, false, true, p, st));
     return LOQT_OK;
 }
 
@@ -378,44 +370,38 @@ loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
         uint16_t* Wb = reinterpret_cast<uint16_t*>(base + L.Wb);
         uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
         const int64_t ldw = (int64_t)round_up(in, 8);
-        if (use_folded(T, out, in)) {
+        const bool folded = use_folded(T, out, in);
+        if (folded) {
             // y = x W_eff^T with W_eff = deq(W) + s deq(P) B folded once per call
-            LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, reinterpret_cast<uint16_t*>(base + L.Bt), Wb, ldw, st));
+            LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, Wb, ldw, true, st));
+        } else {
+            LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wb, LOQT_BF16, ldw, st, SLOT_PREPASS));
+            LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_u, st, SLOT_PREPASS));
+            // U = s x B^T
             memset(&p, 0, sizeof(p));
             p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
-            p.B[0] = bf16_operand(Wb, ldw, (int)out, (int)in);
+            p.B[0] = bf16_operand(B, ld_B, (int)r, (int)in);
             p.M = (int)T;
-            p.N = (int)out;
-            p.alpha = 1.0f;
-            p.C = y;
-            p.ldc = ld_y;
-            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, p, st));
-            return LOQT_OK;
+            p.N = (int)r;
+            p.alpha = s;
+            p.C = U;
+            p.ldc = ld_u;
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_U, EPI_BF16, false, false, p, st));
         }
-        LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wb, LOQT_BF16, ldw, st, SLOT_PREPASS));
-        LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_u, st, SLOT_PREPASS));
-        // U = s x B^T
-        memset(&p, 0, sizeof(p));
-        p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
-        p.B[0] = bf16_operand(B, ld_B, (int)r, (int)in);
-        p.M = (int)T;
-        p.N = (int)r;
-        p.alpha = s;
-        p.C = U;
-        p.ldc = ld_u;
-        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_U, EPI_BF16, p, st));
-        // y = x deq(W)^T + U deq(P)^T
+        // y = x Wb^T (+ U deq(P)^T when the rank-r term is not folded into Wb)
         memset(&p, 0, sizeof(p));
         p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
         p.B[0] = bf16_operand(Wb, ldw, (int)out, (int)in);
-        p.A[1] = bf16_operand(U, ld_u, (int)T, (int)r);
-        p.B[1] = bf16_operand(Pb, ld_u, (int)out, (int)r);
+        if (!folded) {
+            p.A[1] = bf16_operand(U, ld_u, (int)T, (int)r);
+            p.B[1] = bf16_operand(Pb, ld_u, (int)out, (int)r);
+        }
         p.M = (int)T;
         p.N = (int)out;
         p.alpha = 1.0f;
         p.C = y;
         p.ldc = ld_y;
-        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, p, st));
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, false, false, p, st));
         return LOQT_OK;
     }
 
@@ -469,15 +455,11 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
     if (use_prepass(T)) {
         const BwdWs L(T, out, in, r);
         char* base = reinterpret_cast<char*>(ws);
-        uint16_t* Zt = reinterpret_cast<uint16_t*>(base + L.Zt);
-        uint16_t* Pt = reinterpret_cast<uint16_t*>(base + L.Pt);
-        uint16_t* Wt = reinterpret_cast<uint16_t*>(base + L.Wt);
-        uint16_t* Bt = reinterpret_cast<uint16_t*>(base + L.Bt);
-        uint16_t* xt = reinterpret_cast<uint16_t*>(base + L.xt);
+        uint16_t* Wb = reinterpret_cast<uint16_t*>(base + L.Wb);
+        uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
         float* part = reinterpret_cast<float*>(base + L.partials);
-        const int64_t ldo = (int64_t)round_up(out, 8), ldT = (int64_t)round_up(T, 8);
-        // Z = s dy deq(P): B operand is deq(P)^T, r x out
-        LOQT_HIP(launch_dequant_transpose(Pq->codes, Pq->absmax, out, r, Pq->ld, Pt, ldo, st));
+        const int64_t ldw = (int64_t)round_up(in, 8);
+        LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_z, st, SLOT_PREPASS));
         const bool folded = dx && use_folded(T, out, in);
         // Z rides along with dx (one product [dx | Z] over the shared operand dy) when its tiles fit
         // into the last, partly empty round of 256x256 tiles of the dx product; otherwise its own launch
@@ -488,68 +470,57 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
             z_with_dx = t_dx >= 224 && (t_both + 255) / 256 == (t_dx + 255) / 256;
         }
         if (!z_with_dx) {
+            // Z = s dy deq(P): deq(P) is out x r, i.e. K x rows
             memset(&p, 0, sizeof(p));
             p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
-            p.B[0] = bf16_operand(Pt, ldo, (int)r, (int)out);
+            p.B[0] = bf16_operand(Pb, ld_z, (int)r, (int)out);
             p.M = (int)T;
             p.N = (int)r;
             p.alpha = s;
             p.C = Z;
             p.ldc = ld_z;
-            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, p, st));
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, false, true, p, st));
         }
-        if (folded) {
-            // [dx | Z] = dy [W_eff | s deq(P)]: one product over the shared operand dy; W_eff is
-            // folded first and transposed to in x out for the K-contiguous form
-            uint16_t* We = reinterpret_cast<uint16_t*>(base + L.We);
-            const int64_t ldw = (int64_t)round_up(in, 8);
-            LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, reinterpret_cast<uint16_t*>(base + L.Pb), Bt, We, ldw, st));
-            LOQT_HIP(launch_transpose_bf16(We, out, in, ldw, Wt, ldo, st));
+        if (dx) {
+            // dx = dy Wb (+ Z B when the rank-r term is not folded into Wb); Wb is out x in: K x rows
+            if (folded) {
+                LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, Wb, ldw, false, st));
+            } else {
+                LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wb, LOQT_BF16, ldw, st,
+                                           SLOT_PREPASS));
+            }
             memset(&p, 0, sizeof(p));
             p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
-            p.B[0] = bf16_operand(Wt, ldo, (int)in, (int)out);
+            p.B[0] = bf16_operand(Wb, ldw, (int)in, (int)out);
+            if (!folded) {
+                p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
+                p.B[1] = bf16_operand(B, ld_B, (int)in, (int)r);  // r x in: K x rows
+            }
             p.M = (int)T;
             p.N = (int)in;
             p.alpha = 1.0f;
             p.C = dx;
             p.ldc = ld_dx;
-            if (z_with_dx) {
-                p.Bx = bf16_operand(Pt, ldo, (int)r, (int)out);
+            if (z_with_dx) {  // [dx | Z] = dy [W_eff | s deq(P)]
+                p.Bx = bf16_operand(Pb, ld_z, (int)r, (int)out);
                 p.Nx = (int)r;
                 p.alphax = s;
                 p.Cx = Z;
                 p.ldcx = ld_z;
             }
-            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, p, st));
-        } else if (dx) {
-            // dx = dy deq(W) + Z B: B operands are deq(W)^T (in x out) and B^T (in x r)
-            LOQT_HIP(launch_dequant_transpose(Wq->codes, Wq->absmax, out, in, Wq->ld, Wt, ldo, st));
-            LOQT_HIP(launch_transpose_bf16(B, r, in, ld_B, Bt, ld_z, st));
-            memset(&p, 0, sizeof(p));
-            p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
-            p.B[0] = bf16_operand(Wt, ldo, (int)in, (int)out);
-            p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
-            p.B[1] = bf16_operand(Bt, ld_z, (int)in, (int)r);
-            p.M = (int)T;
-            p.N = (int)in;
-            p.alpha = 1.0f;
-            p.C = dx;
-            p.ldc = ld_dx;
-            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, p, st));
+            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, false, true, p, st));
         }
-        // dB = Z^T x: operands Z^T (r x T) and x^T (in x T), contraction over T in slices
-        LOQT_HIP(launch_transpose_bf16(Z, T, r, ld_z, Zt, ldT, st));
-        LOQT_HIP(launch_transpose_bf16(x, T, in, ld_x, xt, ldT, st));
+        // dB = Z^T x: Z is T x r and x is T x in, both K x rows; contraction over T in slices
         memset(&p, 0, sizeof(p));
-        p.A[0] = bf16_operand(Zt, ldT, (int)r, (int)T);
-        p.B[0] = bf16_operand(xt, ldT, (int)in, (int)T);
+        p.A[0] = bf16_operand(Z, ld_z, (int)r, (int)T);
+        p.B[0] = bf16_operand(x, ld_x, (int)in, (int)T);
         p.M = (int)r;
         p.N = (int)in;
         p.alpha = 1.0f;
         p.C = part;
         p.ldc = L.ldp;
         p.splits = L.splits;
-        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DB, EPI_F32_SPLITK, p, st));
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DB, EPI_F32_SPLITK, true, true, p, st));
         LOQT_HIP(launch_reduce_db(part, L.splits, r, in, L.ldp, dB, dB_dtype, ld_dB, accumulate, st));
         return LOQT_OK;
     }

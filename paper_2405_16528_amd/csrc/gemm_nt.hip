@@ -20,6 +20,8 @@
 //    16-byte-per-lane row segments; the merge epilogue requantises 64-blocks in registers;
 //  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in 8-row groups so that the
 //    work-groups sharing an L2 also share operand panels.
+#include <type_traits>
+
 #include "loqt_internal.h"
 
 namespace loqt {
@@ -32,15 +34,15 @@ constexpr int ROWB = 128;  // bytes of one LDS row (64 bf16)
 #define LOQT_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define LOQT_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-// one MFMA, one LDS read, eight times; then the remaining eight MFMAs
-#define LOQT_SCHED_GROUP()                                        \
-    do {                                                          \
-        _Pragma("unroll") for (int q_ = 0; q_ < 8; ++q_) {        \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    \
-        }                                                         \
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);        \
-        __builtin_amdgcn_sched_barrier(0);                        \
+// interleave the NR fragment reads of the next k16 step one-to-one with the NM MFMAs of this one
+#define LOQT_SCHED_GROUP()                                               \
+    do {                                                                 \
+        _Pragma("unroll") for (int q_ = 0; q_ < NR; ++q_) {              \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           \
+        }                                                                \
+        if (NM > NR) __builtin_amdgcn_sched_group_barrier(0x008, NM - NR, 0); \
+        __builtin_amdgcn_sched_barrier(0);                               \
     } while (0)
 
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
@@ -63,10 +65,11 @@ struct NtCfg {
     static constexpr int SMEM = (SMEM_MAIN > SMEM_EPI ? SMEM_MAIN : SMEM_EPI) + 64;
 };
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool ARC, bool BRC>
 __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     using Cfg = NtCfg<BM, BN>;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE, NCH = Cfg::NCH, NCHA = Cfg::NCHA;
+    constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE;
+    constexpr int NM = TM * TN, NR = TM * (ARC ? 2 : 1) + TN * (BRC ? 2 : 1);  // MFMAs / LDS reads per k16 step
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -108,67 +111,125 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // ---- staging: chunk i of this thread is LDS slot (i*256 + tid): row slot>>3, physical
-    // chunk slot&7, logical chunk (slot&7) ^ swz(row).  i*32 rows apart, so the chunk column
-    // is the same for every i.
-    const int r0 = tid >> 3;
-    const int kc = (tid & 7) ^ swz(r0);
-    auto stage_tile = [&](int kt, char* stage) {
-        const int seg = kt >= nkt0 ? 1 : 0;
-        const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
-        const Operand& A = p.A[seg];
-        const Operand& B = part1 ? p.Bx : p.B[seg];
-        const int kleft = A.K - k0;
-        const uint16_t* pa = reinterpret_cast<const uint16_t*>(A.ptr) + k0 + kc * 8;
-        const uint16_t* pb = reinterpret_cast<const uint16_t*>(B.ptr) + k0 + kc * 8;
-        if (kleft >= BK) {
+    // ---- staging.  Chunk i of this thread is LDS slot (i*256 + tid) of the operand tile (the LDS side
+    // of a direct load is lane-linear); which 16 bytes of global memory go there carries the swizzle.
+    //  K-contiguous operand (rows x K): tile [row][64 k], slot -> row slot>>3, physical chunk slot&7,
+    //    logical chunk (slot&7) ^ swz(row); rows are i*32 apart, so the chunk column is the same for all i.
+    //  row-contiguous operand (K x rows): tile [64 k][BR rows], slot -> k = slot / (BR/8), physical chunk
+    //    slot % (BR/8), logical chunk physical ^ 2*(k&3); read back transposed by ds_read_b64_tr_b16.
+    auto stage_operand = [&](auto rc_tag, auto br_tag, const Operand& O, int row0, int k0, char* tile) {
+        constexpr bool RC = decltype(rc_tag)::value;
+        constexpr int BR = decltype(br_tag)::value;
+        constexpr int NC = BR / 32;  // chunks per thread
+        const int kleft = O.K - k0;
+        const uint16_t* base = reinterpret_cast<const uint16_t*>(O.ptr);
+        if constexpr (!RC) {
+            const int r0 = tid >> 3;
+            const int kc = (tid & 7) ^ swz(r0);
+            const uint16_t* pk = base + k0 + kc * 8;
+            if (kleft >= BK) {
 #pragma unroll
-            for (int i = 0; i < NCH; ++i) {
-                const bool isA = i < NCHA;
-                const int row = (isA ? m0 + i * 32 : n0 + (i - NCHA) * 32) + r0;
-                const int rc = min(row, (isA ? A.rows : B.rows) - 1);  // rows past the end: any valid row
-                const uint16_t* g = (isA ? pa : pb) + (int64_t)rc * (isA ? A.ld : B.ld);
-                __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(g), LOQT_LDS_PTR(stage + i * 4096 + wave * 1024), 16, 0,
-                                                 0);
+                for (int i = 0; i < NC; ++i) {
+                    const int rcl = min(row0 + i * 32 + r0, O.rows - 1);  // rows past the end: any valid row
+                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(pk + (int64_t)rcl * O.ld),
+                                                     LOQT_LDS_PTR(tile + i * 4096 + wave * 1024), 16, 0, 0);
+                }
+            } else {
+                // K tail: through registers, elements past K zeroed
+                const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
+#pragma unroll 1
+                for (int i = 0; i < NC; ++i) {
+                    const int rcl = min(row0 + i * 32 + r0, O.rows - 1);
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (nv > 0) {
+                        v = *reinterpret_cast<const uint4*>(pk + (int64_t)rcl * O.ld);
+                        uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+#pragma unroll
+                        for (int d = 0; d < 4; ++d) {
+                            if (2 * d >= nv) w[d] = 0;
+                            else if (2 * d + 1 >= nv) w[d] &= 0xffffu;
+                        }
+                    }
+                    *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
+                }
             }
         } else {
-            // K tail: through registers, elements past K zeroed in both operands
-            const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
-#pragma unroll 1
-            for (int i = 0; i < NCH; ++i) {
-                const bool isA = i < NCHA;
-                const int row = (isA ? m0 + i * 32 : n0 + (i - NCHA) * 32) + r0;
-                const int rc = min(row, (isA ? A.rows : B.rows) - 1);
-                uint4 v = make_uint4(0, 0, 0, 0);
-                if (nv > 0) {
-                    v = *reinterpret_cast<const uint4*>((isA ? pa : pb) + (int64_t)rc * (isA ? A.ld : B.ld));
-                    uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+            constexpr int CPR = BR / 8;       // chunks per k row
+            constexpr int KPI = 256 / CPR;    // k rows covered by one pass of the 256 threads
+            const int kq = tid / CPR;         // k of chunk i is i*KPI + kq  (KPI is a multiple of 4)
+            const int logical = (tid % CPR) ^ (2 * (kq & 3));
+            const int cmax = ((O.rows - 1) >> 3) << 3;
+            const int col = min(row0 + logical * 8, cmax);  // columns past the end: any valid chunk
+            const uint16_t* pk = base + (int64_t)(k0 + kq) * O.ld + col;
+            if (kleft >= BK) {
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        if (2 * d >= nv) w[d] = 0;
-                        else if (2 * d + 1 >= nv) w[d] &= 0xffffu;
-                    }
+                for (int i = 0; i < NC; ++i)
+                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(pk + (int64_t)(i * KPI) * O.ld),
+                                                     LOQT_LDS_PTR(tile + i * 4096 + wave * 1024), 16, 0, 0);
+            } else {
+#pragma unroll 1
+                for (int i = 0; i < NC; ++i) {
+                    uint4 v = make_uint4(0, 0, 0, 0);
+                    if (i * KPI + kq < kleft) v = *reinterpret_cast<const uint4*>(pk + (int64_t)(i * KPI) * O.ld);
+                    *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
                 }
-                *reinterpret_cast<uint4*>(stage + i * 4096 + tid * 16) = v;
             }
         }
     };
+    auto stage_tile = [&](int kt, char* stage) {
+        const int seg = kt >= nkt0 ? 1 : 0;
+        const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
+        stage_operand(std::integral_constant<bool, ARC>{}, std::integral_constant<int, BM>{}, p.A[seg], m0, k0, stage);
+        stage_operand(std::integral_constant<bool, BRC>{}, std::integral_constant<int, BN>{},
+                      part1 ? p.Bx : p.B[seg], n0, k0, stage + BM * ROWB);
+    };
 
-    // ---- fragments: row (lane & 31), logical chunk 2*ks + (lane >> 5)
+    // ---- fragments.  A lane holds row (lane & 31) of a 32-row fragment and the 8 k-values
+    // 16*ks + 8*(lane >> 5) .. +7.  K-contiguous tiles: one 16-byte read of logical chunk 2*ks + (lane>>5).
+    // Row-contiguous tiles: two transposing 8-byte reads; within a group of 16 lanes, lane 4*j + q supplies
+    // the address of k row j, columns 4q..4q+3 and receives the four k of column (lane & 15).
     const int frow = lane & 31;
     const int h = lane >> 5;
     const int fsw = h ^ swz(frow);
     const int a_off = (wm * Cfg::WTM + frow) * ROWB;
     const int b_off = BM * ROWB + (wn * Cfg::WTN + frow) * ROWB;
+    int a_rc[TM], b_rc[TN];
+    {
+        const int jj = (lane >> 2) & 3, q = lane & 3, cb = ((lane >> 4) & 1) * 16;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int chunk = ((wm * Cfg::WTM + i * 32 + cb) >> 3) + (q >> 1);
+            a_rc[i] = (8 * h + jj) * (BM * 2) + ((chunk ^ (2 * jj)) << 4) + (q & 1) * 8;
+        }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int chunk = ((wn * Cfg::WTN + j * 32 + cb) >> 3) + (q >> 1);
+            b_rc[j] = BM * ROWB + (8 * h + jj) * (BN * 2) + ((chunk ^ (2 * jj)) << 4) + (q & 1) * 8;
+        }
+    }
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    auto read_tr = [&](const char* ptr, int pitch) -> bf16x8 {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(ptr));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(ptr + 4 * pitch));
+        const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, v);
+    };
     bf16x8 fa[2][TM], fb[2][TN];
     auto load_frags = [&](const char* stage, int ks, int buf) {
         const int coff = ((2 * ks) ^ fsw) << 4;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 32 * ROWB + coff);
+        for (int i = 0; i < TM; ++i) {
+            if constexpr (ARC) fa[buf][i] = read_tr(stage + a_rc[i] + 16 * ks * (BM * 2), BM * 2);
+            else fa[buf][i] = *reinterpret_cast<const bf16x8*>(stage + a_off + i * 32 * ROWB + coff);
+        }
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 32 * ROWB + coff);
+        for (int j = 0; j < TN; ++j) {
+            if constexpr (BRC) fb[buf][j] = read_tr(stage + b_rc[j] + 16 * ks * (BN * 2), BN * 2);
+            else fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 32 * ROWB + coff);
+        }
     };
     // transposed accumulation: D^T = B_frag A_frag^T, so lane = m, registers = n
     auto mfmas = [&](int buf) {
@@ -363,9 +424,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool ARC, bool BRC>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    auto kern = nt_gemm_kernel<BM, BN, EPI>;
+    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC>;
     constexpr int smem = NtCfg<BM, BN>::SMEM;
     static bool attr_set = false;
     if (!attr_set) {
@@ -380,27 +441,40 @@ hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <int EPI>
+template <int EPI, bool ARC, bool BRC>
 hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     // largest tile that still gives every compute unit a work-group
     const int64_t z = EPI == EPI_F32_SPLITK ? p.splits : 1;
     auto tiles = [&](int bm, int bn) {
         return z * ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn + (p.Nx + bn - 1) / bn);
     };
-    if (tiles(256, 256) >= 224) return launch_nt<256, 256, EPI>(p, st);
-    if (tiles(256, 128) >= 224) return launch_nt<256, 128, EPI>(p, st);
-    return launch_nt<128, 128, EPI>(p, st);
+    if (tiles(256, 256) >= 224) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
+    if (tiles(256, 128) >= 224) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
+    return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
 }
 
 }  // namespace
 
-hipError_t launch_gemm_nt(int slot, int epi, const GemmParams& p, hipStream_t st) {
+// a_rc / b_rc: the operand is stored K x rows (rows contiguous) instead of rows x K
+hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st) {
     TimedLaunch tl(slot, st);
-    switch (epi) {
-        case EPI_BF16: return launch_nt_sized<EPI_BF16>(p, st);
-        case EPI_F32_SPLITK: return launch_nt_sized<EPI_F32_SPLITK>(p, st);
-        case EPI_MERGE: return launch_nt_sized<EPI_MERGE>(p, st);
-        case EPI_FOLD: return launch_nt_sized<EPI_FOLD>(p, st);
+    if (!a_rc && !b_rc) {
+        switch (epi) {
+            case EPI_BF16: return launch_nt_sized<EPI_BF16, false, false>(p, st);
+            default: break;
+        }
+    } else if (!a_rc && b_rc) {
+        switch (epi) {
+            case EPI_BF16: return launch_nt_sized<EPI_BF16, false, true>(p, st);
+            case EPI_MERGE: return launch_nt_sized<EPI_MERGE, false, true>(p, st);
+            case EPI_FOLD: return launch_nt_sized<EPI_FOLD, false, true>(p, st);
+            default: break;
+        }
+    } else if (a_rc && b_rc) {
+        switch (epi) {
+            case EPI_F32_SPLITK: return launch_nt_sized<EPI_F32_SPLITK, true, true>(p, st);
+            default: break;
+        }
     }
     return hipErrorInvalidValue;
 }

@@ -182,11 +182,8 @@ hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_
                             int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st);
 int gemm_db_splits(int64_t T, int64_t r, int64_t in);
 
-// large-token path (gemm_nt.hip, prepass.hip): operands bf16, rows x K with K contiguous
-hipError_t launch_gemm_nt(int slot, int epi, const GemmParams& p, hipStream_t st);
-hipError_t launch_dequant_transpose(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
-                                    int64_t ld_q, uint16_t* dst, int64_t ld_d, hipStream_t st);
-hipError_t launch_transpose_bf16(const uint16_t* src, int64_t rows, int64_t cols, int64_t ld_s, uint16_t* dst,
-                                 int64_t ld_d, hipStream_t st);
+// large-token path (gemm_nt.hip): bf16 operands stored rows x K (K contiguous) or, with the
+// a_rc / b_rc flag, K x rows (rows contiguous; Operand::ld is the pitch of that stored matrix)
+hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st);
 
 }  // namespace loqt
