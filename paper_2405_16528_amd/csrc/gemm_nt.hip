@@ -117,21 +117,25 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     //    logical chunk (slot&7) ^ swz(row); rows are i*32 apart, so the chunk column is the same for all i.
     //  row-contiguous operand (K x rows): tile [64 k][BR rows], slot -> k = slot / (BR/8), physical chunk
     //    slot % (BR/8), logical chunk physical ^ 2*(k&3); read back transposed by ds_read_b64_tr_b16.
+    // Addresses are a wave-uniform 64-bit base (operand pointer + tile origin + K offset, scalar
+    // registers) plus a 32-bit per-lane byte offset inside the tile's rows, so the loads use the
+    // scalar-base form and no 64-bit address arithmetic runs on the vector unit.
     auto stage_operand = [&](auto rc_tag, auto br_tag, const Operand& O, int row0, int k0, char* tile) {
         constexpr bool RC = decltype(rc_tag)::value;
         constexpr int BR = decltype(br_tag)::value;
         constexpr int NC = BR / 32;  // chunks per thread
         const int kleft = O.K - k0;
-        const uint16_t* base = reinterpret_cast<const uint16_t*>(O.ptr);
+        const uint32_t ld2 = (uint32_t)O.ld * 2u;  // row pitch in bytes (a tile spans < 2^32 bytes)
         if constexpr (!RC) {
             const int r0 = tid >> 3;
             const int kc = (tid & 7) ^ swz(r0);
-            const uint16_t* pk = base + k0 + kc * 8;
+            const int rlast = O.rows - 1 - row0;  // rows past the end: any valid row
+            const char* sbase = reinterpret_cast<const char*>(O.ptr) + ((int64_t)row0 * O.ld + k0) * 2;
             if (kleft >= BK) {
 #pragma unroll
                 for (int i = 0; i < NC; ++i) {
-                    const int rcl = min(row0 + i * 32 + r0, O.rows - 1);  // rows past the end: any valid row
-                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(pk + (int64_t)rcl * O.ld),
+                    const uint32_t off = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
+                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(sbase + off),
                                                      LOQT_LDS_PTR(tile + i * 4096 + wave * 1024), 16, 0, 0);
                 }
             } else {
@@ -139,10 +143,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
 #pragma unroll 1
                 for (int i = 0; i < NC; ++i) {
-                    const int rcl = min(row0 + i * 32 + r0, O.rows - 1);
+                    const uint32_t off = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
                     uint4 v = make_uint4(0, 0, 0, 0);
                     if (nv > 0) {
-                        v = *reinterpret_cast<const uint4*>(pk + (int64_t)rcl * O.ld);
+                        v = *reinterpret_cast<const uint4*>(sbase + off);
                         uint32_t* w = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
                         for (int d = 0; d < 4; ++d) {
@@ -158,19 +162,20 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             constexpr int KPI = 256 / CPR;    // k rows covered by one pass of the 256 threads
             const int kq = tid / CPR;         // k of chunk i is i*KPI + kq  (KPI is a multiple of 4)
             const int logical = (tid % CPR) ^ (2 * (kq & 3));
-            const int cmax = ((O.rows - 1) >> 3) << 3;
-            const int col = min(row0 + logical * 8, cmax);  // columns past the end: any valid chunk
-            const uint16_t* pk = base + (int64_t)(k0 + kq) * O.ld + col;
+            const int clast = (((O.rows - 1) >> 3) << 3) - row0;  // columns past the end: any valid chunk
+            const char* sbase = reinterpret_cast<const char*>(O.ptr) + ((int64_t)k0 * O.ld + row0) * 2;
+            const uint32_t off0 = (uint32_t)kq * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
             if (kleft >= BK) {
 #pragma unroll
                 for (int i = 0; i < NC; ++i)
-                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(pk + (int64_t)(i * KPI) * O.ld),
+                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(sbase + (off0 + (uint32_t)(i * KPI) * ld2)),
                                                      LOQT_LDS_PTR(tile + i * 4096 + wave * 1024), 16, 0, 0);
             } else {
 #pragma unroll 1
                 for (int i = 0; i < NC; ++i) {
                     uint4 v = make_uint4(0, 0, 0, 0);
-                    if (i * KPI + kq < kleft) v = *reinterpret_cast<const uint4*>(pk + (int64_t)(i * KPI) * O.ld);
+                    if (i * KPI + kq < kleft)
+                        v = *reinterpret_cast<const uint4*>(sbase + (off0 + (uint32_t)(i * KPI) * ld2));
                     *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
                 }
             }
