@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 METRIC = "LoQT NF4 linear fwd+bwd TFLOP/s at 7B shapes; merge+requant GB/s"
 
 # HBM-side traffic of the dominant kernel per launch, from profiles/bench_7b_block_hbm_traffic.md
-# (fetch 873.0 MB + write 94.2 MB); null for workloads that were not profiled.
-TRAFFIC_BYTES_PER_LAUNCH = {"7b_block": 967.2e6}
+# (fetch 749.8 MB + write 101.8 MB); null for workloads that were not profiled.
+TRAFFIC_BYTES_PER_LAUNCH = {"7b_block": 851.6e6}
 
 
 def parse():
@@ -199,14 +199,14 @@ def main():
         if name in kflops:
             ent["tflops"] = kflops[name] * args.steps / (ms * 1e-3) / 1e12
         kernels[name] = ent
-    # dominant kernel: the 256x256 bf16-epilogue instantiation serves both gemm_y and gemm_dx
-    dom_slots = [k for k in ("gemm_y", "gemm_z+dx") if k in kernels]
+    # dominant kernel: the K-contiguous 256x256 bf16-epilogue instantiation, i.e. the gemm_y launches
+    dom_slots = [k for k in ("gemm_y",) if k in kernels]
     dom_ms = sum(kernels[k]["ms_per_step"] for k in dom_slots)
     dom_launches = sum(kernels[k]["launches_per_step"] for k in dom_slots)
     dom_flops = sum(kflops[k] for k in dom_slots)
     dom_tflops = dom_flops / (dom_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "nt_gemm_kernel<*,*,EPI_BF16> (gemm_y, gemm_dx and gemm_z launches)", "bound": "mfma",
+        "kernel": "nt_gemm_kernel<256,256,EPI_BF16,false,false> (the gemm_y launches: y = x W_eff^T)", "bound": "mfma",
         "achieved": dom_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
         "frac": dom_tflops / PEAK_BF16_TFLOPS,
         "flops_per_launch": dom_flops / dom_launches, "avg_launch_ms": dom_ms / dom_launches,
