@@ -1,23 +1,26 @@
-// Fast path for large token counts: every product of the layer as a plain "NT" bf16 GEMM
+// Fast path for large token counts: every product of the layer as a plain bf16 GEMM
 //
-//   C[M x N] = alpha * sum_seg  A_seg[M x K_seg] * B_seg[N x K_seg]^T      (fp32 accumulate)
+//   C[M x N] = alpha * sum_seg  A_seg[M x K_seg] * B_seg[K_seg x N]        (fp32 accumulate)
 //
-// with both operands bf16 and contiguous along K.  NF4 operands are dequantised to bf16 once
-// per call by a streaming pre-pass (prepass.hip) instead of once per output tile; at thousands
-// of tokens that pass costs a few per cent of the GEMM and keeps every VALU and LDS cycle of the
-// inner loop for feeding the matrix cores.
+// with both operands bf16, each stored either rows x K (K contiguous) or K x rows (rows contiguous).
+// NF4 operands are dequantised to bf16 once per call (nf4_dequantize_kernel, or the fold epilogue
+// below) instead of once per output tile; at thousands of tokens that costs a few per cent of the
+// GEMM and keeps every VALU and LDS cycle of the inner loop for feeding the matrix cores.
 //
 // Work-group: 256 threads = 4 waves (2 x 2), tile BM x BN x 64, v_mfma_f32_32x32x16_bf16.
 //  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
 //    registers, no ds_write); two LDS stages, the loads of tile t+2 are issued as soon as the
 //    barrier of tile t has released its stage, so they have a whole tile of MFMAs to land;
-//  * 16-byte chunks of a 128-byte LDS row are XOR-swizzled; the swizzle is applied on the
-//    global side (which chunk a lane fetches), the LDS side of a direct load is lane-linear;
+//  * 16-byte chunks of an LDS row are XOR-swizzled; the swizzle is applied on the global side
+//    (which chunk a lane fetches), the LDS side of a direct load is lane-linear;
+//  * K-contiguous tiles are read back with one 16-byte read per fragment, row-contiguous tiles
+//    with two transposing reads (ds_read_b64_tr_b16): no operand is ever transposed in memory;
 //  * MFMA fragments are double-buffered in registers one k16 step ahead, reads interleaved
 //    one-to-one with the MFMAs of the running step (sched_group_barrier);
 //  * the accumulators are kept transposed (lane = row m, registers = 4 consecutive n) so the
 //    epilogues can pack along n: bf16 results are staged through LDS and leave as whole
-//    16-byte-per-lane row segments; the merge epilogue requantises 64-blocks in registers;
+//    16-byte-per-lane row segments; the fold epilogue adds the dequantised NF4 weight on the way;
+//    the merge epilogue requantises 64-blocks in registers (paper sec. 5.1, Alg. 1 line 5);
 //  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in 8-row groups so that the
 //    work-groups sharing an L2 also share operand panels.
 #include <type_traits>
