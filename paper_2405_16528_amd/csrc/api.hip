@@ -131,21 +131,12 @@ struct BwdWs {
         Pb = Wb + bf16_bytes(out, in);
         partials = Pb + bf16_bytes(out, r);
         ldp = (int64_t)round_up(in, 4);
-        // split the contraction over T: the fewest slices whose work-group count fills whole
-        // rounds of the 256 compute units to at least 90 % (each slice at least 512 deep)
-        const int64_t tiles = ((r + 255) / 256) * ((in + 255) / 256);
+        // split the contraction over T so that about two 128x128 work-groups per compute unit are
+        // resident (at least two slices, each at least 512 deep)
+        const int64_t tiles = ((r + 127) / 128) * ((in + 127) / 128);
         const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, T / 512));
-        int64_t s = 1;
-        double best = 0.0;
-        for (int64_t c = 1; c <= max_s; ++c) {
-            const int64_t w = tiles * c;
-            const double eff = (double)w / (double)(((w + 255) / 256) * 256);
-            if (eff > best + 1e-9) {
-                best = eff;
-                s = c;
-            }
-            if (eff >= 0.9) break;
-        }
+        int64_t s = std::max<int64_t>(2, (512 + tiles / 2) / tiles);
+        s = std::min(s, max_s);
         splits = (int)s;
         total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
     }

@@ -449,6 +449,10 @@ hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
+}  // namespace
+extern int g_nt_tile_override;
+namespace {
+
 template <int EPI, bool ARC, bool BRC>
 hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     // largest tile that still gives every compute unit a work-group
@@ -456,12 +460,25 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     auto tiles = [&](int bm, int bn) {
         return z * ((p.M + bm - 1) / bm) * ((p.N + bn - 1) / bn + (p.Nx + bn - 1) / bn);
     };
-    if (tiles(256, 256) >= 224) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
-    if (tiles(256, 128) >= 224) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
+    // 256x256 tiles (one work-group per compute unit) have the best ratio of MFMA work to LDS and
+    // global traffic and win on long contractions with a light epilogue.  With short contractions
+    // or a heavy epilogue (merge, fp32 slices; measured on real data, the fold is better off with the
+    // large tile) two or three resident 128x128 work-groups per
+    // compute unit win: the epilogue and prologue of one overlap with the main loop of another.
+    int choice = g_nt_tile_override;
+    if (choice == 0) {
+        const int K = p.A[0].K + p.A[1].K;
+        const bool light = (EPI == EPI_BF16 && K >= 2048) || EPI == EPI_FOLD;
+        choice = (light && tiles(256, 256) >= 224) ? 1 : 3;
+    }
+    if (choice == 1) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
+    if (choice == 2) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
     return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
 }
 
 }  // namespace
+
+int g_nt_tile_override = 0;
 
 // a_rc / b_rc: the operand is stored K x rows (rows contiguous) instead of rows x K
 hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st) {

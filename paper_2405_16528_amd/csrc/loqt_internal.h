@@ -185,5 +185,7 @@ int gemm_db_splits(int64_t T, int64_t r, int64_t in);
 // large-token path (gemm_nt.hip): bf16 operands stored rows x K (K contiguous) or, with the
 // a_rc / b_rc flag, K x rows (rows contiguous; Operand::ld is the pitch of that stored matrix)
 hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st);
+// tuning aid for benchmarks: 0 = choose by shape, 1 = 256x256, 2 = 256x128, 3 = 128x128 tiles
+extern int g_nt_tile_override;
 
 }  // namespace loqt
