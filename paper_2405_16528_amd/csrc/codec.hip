@@ -13,6 +13,9 @@ __global__ __launch_bounds__(256) void nf4_quantize_kernel(const float* __restri
                                                            int cols, int64_t ld_w,
                                                            uint8_t* __restrict__ codes,
                                                            float* __restrict__ absmax, int64_t ld_q) {
+    __shared__ Nf4EncTables enc;
+    if (threadIdx.x < 64) nf4_enc_tables_fill(&enc, threadIdx.x);
+    __syncthreads();
     const int nbr = (int)(ld_q >> 6);  // blocks per row, padding included
     const int64_t nblocks = rows * nbr;
     const int sub = threadIdx.x & 7;
@@ -38,18 +41,13 @@ __global__ __launch_bounds__(256) void nf4_quantize_kernel(const float* __restri
         m = fmaxf(m, __shfl_xor(m, 1));
         m = fmaxf(m, __shfl_xor(m, 2));
         m = fmaxf(m, __shfl_xor(m, 4));
-        uint32_t word = 0x77777777u;
-        if (m > 0.f) {
-            Nf4Thresholds th;
-            th.set(m);
-            word = 0;
+        // elements past `cols` were read as 0 and encode to 7 like any zero
+        Nf4BlockEncoder be;
+        be.set(m);
+        uint32_t c[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                uint32_t c = (j0 + e < cols) ? th.encode(v[e]) : 7u;
-                // element e lives in byte e/2; even e in the high nibble
-                word |= c << (8 * (e >> 1) + ((e & 1) ? 0 : 4));
-            }
-        }
+        for (int e = 0; e < 8; ++e) c[e] = be.encode(&enc, v[e]);
+        const uint32_t word = nf4_pack4(c[0], c[1], c[2], c[3]) | (nf4_pack4(c[4], c[5], c[6], c[7]) << 16);
         *reinterpret_cast<uint32_t*>(codes + row * (ld_q >> 1) + (j0 >> 1)) = word;
         if (sub == 0) absmax[row * nbr + bcol] = m;
     }

@@ -334,6 +334,9 @@ __global__ __launch_bounds__(256) void loqt_gemm_kernel(const GemmParams p) {
         // merge: rows of the tile run along `in` (the block direction of W), columns are
         // rows of W.  A 64-block of W row n lives in two vertically adjacent 32x32 tiles of
         // one wave: 32 values in this lane, 32 in lane ^ 32.
+        Nf4EncTables* enc = reinterpret_cast<Nf4EncTables*>(smem);  // the stages are free now
+        if (tid < 64) nf4_enc_tables_fill(enc, tid);
+        __syncthreads();
         const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
 #pragma unroll
         for (int tj = 0; tj < TN; ++tj) {
@@ -354,8 +357,8 @@ __global__ __launch_bounds__(256) void loqt_gemm_kernel(const GemmParams p) {
                     if (live) cw[q] = *reinterpret_cast<const uint16_t*>(p.w_codes + n * ldb + (mq >> 1));
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float wold = am_old * lut[nib(cw[q], j)];
-                        float val = wold + p.alpha * acc[2 * b + (q >> 2)][tj][4 * (q & 3) + j];
+                        float val = __builtin_fmaf(p.alpha, acc[2 * b + (q >> 2)][tj][4 * (q & 3) + j],
+                                                   am_old * lut[nib(cw[q], j)]);
                         if (mq + j >= p.w_cols) val = 0.f;
                         v[4 * q + j] = val;
                     }
@@ -364,18 +367,14 @@ __global__ __launch_bounds__(256) void loqt_gemm_kernel(const GemmParams p) {
 #pragma unroll
                 for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(v[e]));
                 amax = fmaxf(amax, __shfl_xor(amax, 32));
-                Nf4Thresholds th;
-                th.set(amax);
+                Nf4BlockEncoder be;
+                be.set(amax);
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {
                     const int mq = mb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
-                    uint32_t word = 0;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        uint32_t code = 7u;
-                        if (amax > 0.f && mq + j < p.w_cols) code = th.encode(v[4 * q + j]);
-                        word |= code << (8 * (j >> 1) + ((j & 1) ? 0 : 4));
-                    }
+                    // zeros (an all-zero block, columns past the end) encode to 7 by themselves
+                    const uint32_t word = nf4_pack4(be.encode(enc, v[4 * q + 0]), be.encode(enc, v[4 * q + 1]),
+                                                    be.encode(enc, v[4 * q + 2]), be.encode(enc, v[4 * q + 3]));
                     if (live) *reinterpret_cast<uint16_t*>(p.out_codes + n * ldb + (mq >> 1)) = (uint16_t)word;
                 }
                 if (live && h == 0) p.out_absmax[n * lda + (mb >> 6)] = amax;

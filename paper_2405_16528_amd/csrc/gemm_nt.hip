@@ -364,8 +364,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     } else {
         // merge (M = out, N = in): W_new = fl32(absmax * q[code]) + alpha * acc, requantised per
         // 64-block along n.  A block of row m is 32 values in this lane and 32 in lane ^ 32.
-        float* lut = reinterpret_cast<float*>(smem);
-        if (tid < 16) lut[tid] = kNf4Levels[tid];
+        Nf4EncTables* enc = reinterpret_cast<Nf4EncTables*>(smem);
+        float* lut = reinterpret_cast<float*>(smem + sizeof(Nf4EncTables));
+        if (tid < 64) nf4_enc_tables_fill(enc, tid);
+        else if (tid < 80) lut[tid - 64] = kNf4Levels[tid - 64];
         __syncthreads();
         const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
 #pragma unroll
@@ -389,36 +391,35 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 float v[32];
 #pragma unroll
                 for (int q = 0; q < 8; ++q) {  // q = 4*tt + g: tile tt of the pair, column group g
-                    const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
                     const uint32_t cw = (reinterpret_cast<const uint32_t*>(&cw4[q >> 2])[q & 3] >> (16 * h)) & 0xffffu;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const float wold = am_old * lut[nib4(cw, j)];
-                        float val = wold + p.alpha * acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j];
-                        if (nq + j >= p.w_cols) val = 0.f;
-                        v[4 * q + j] = val;
+                    for (int j = 0; j < 4; ++j)
+                        v[4 * q + j] = __builtin_fmaf(p.alpha, acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j],
+                                                      am_old * lut[nib4(cw, j)]);
+                }
+                if (nb + 64 > p.w_cols) {  // ragged last block (wave-uniform): columns past the end count as 0
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (nq + j >= p.w_cols) v[4 * q + j] = 0.f;
                     }
                 }
                 float amax = 0.f;
 #pragma unroll
                 for (int e = 0; e < 32; ++e) amax = fmaxf(amax, fabsf(v[e]));
                 amax = fmaxf(amax, __shfl_xor(amax, 32));
-                Nf4Thresholds th;
-                th.set(amax);
+                Nf4BlockEncoder be;
+                be.set(amax);
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
                     uint32_t o[4];
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int q = 4 * tt + g;
-                        const int nq = nb + tt * 32 + 8 * g + 4 * h;
-                        uint32_t word = 0;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            uint32_t code = 7u;
-                            if (amax > 0.f && nq + j < p.w_cols) code = th.encode(v[4 * q + j]);
-                            word |= code << (8 * (j >> 1) + ((j & 1) ? 0 : 4));
-                        }
+                        uint32_t word = nf4_pack4(be.encode(enc, v[4 * q + 0]), be.encode(enc, v[4 * q + 1]),
+                                                  be.encode(enc, v[4 * q + 2]), be.encode(enc, v[4 * q + 3]));
                         word <<= 16 * h;                       // this lane's half of dword g
                         o[g] = word | __shfl_xor(word, 32);    // the partner lane holds the other half
                     }

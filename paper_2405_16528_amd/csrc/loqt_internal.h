@@ -53,49 +53,64 @@ __device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v 
 __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
 
 // ---------------------------------------------------------------------------------------
-// Exact NF4 encoder.
+// Exact NF4 encoder (paper sec. 5.1: code = argmin_i |w / M - q_i|, ties to the lower index).
 //
-// The code of w in a block with scale M > 0 is #{ j : w > mid_j * M } with the comparison in
-// real arithmetic.  mid_j * M is exact in fp64 (29 x 24 significant bits).  For an fp32 w,
-//     w > t   <=>   w > RD32(t)         (RD32 = round toward -inf to fp32)
-// because no fp32 number lies strictly between RD32(t) and t.  So the 15 thresholds are
-// rounded down to fp32 once per block and every element then needs fp32 compares only.
+// The code of w in a block with scale M > 0 is #{ j : w > mid_j * M } with the comparison in real
+// arithmetic, mid_j = (q_j + q_{j+1}) / 2.  Instead of 15 comparisons (or a 4-level select tree over
+// 15 per-block thresholds) each element takes about 8 vector operations and two LDS reads:
+// with u = w / M in [-1, 1], cut the axis into buckets of width 1/16 whose edges sit at odd
+// multiples of 1/32: bucket k = RN(16 u) + 16.  The 15 decision points mid_j are at least 0.0805
+// apart and none is closer than 0.004 to a bucket edge, so a bucket holds at most one of them and
+// the code of every w that lands in bucket k is
+//     c0[k] + [ w > mid[k] * M ],     c0[k] = #{ j : mid_j left of the bucket },
+//     mid[k] = mid_{c0[k]}  (+inf when c0[k] = 15; when the bucket holds no decision point the next
+//              one to the right is used and the comparison is simply false).
+// The bucket index only has to be right up to the guard band (it is computed from an approximate
+// reciprocal); the deciding comparison is exact: mid * M is a 29 x 24 bit product, exact in fp64,
+// and w converts exactly.  All of it runs in fp64, so every finite fp32 block (denormal or huge
+// scale included) takes the same path.  A zero block is encoded against M = 1: every element is 0,
+// lands in the bucket around 0 and gets code 7.  The same holds for zero padding inside a live block.
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ float nf4_threshold(double mid, float absmax) {
-    const double t = mid * (double)absmax;  // exact
-    float f = (float)t;                     // round to nearest
-    if ((double)f > t) {                    // went up: step to the next fp32 below
-        uint32_t u = __float_as_uint(f);
-        u = (f > 0.0f) ? u - 1u : ((f < 0.0f) ? u + 1u : 0x80000001u);
-        f = __uint_as_float(u);
-    }
-    return f;
+struct Nf4EncTables {
+    double mid[64];
+    uint32_t c0[64];
+};
+
+// one entry per calling thread, k = 0..63 (entries above 32 are never addressed by finite data
+// but keep every masked index inside the table)
+__device__ __forceinline__ void nf4_enc_tables_fill(Nf4EncTables* t, int k) {
+    const double left = ((double)k - 16.5) * 0.0625 - 1e-4;  // left edge of bucket k, widened by the guard
+    int c = 0;
+#pragma unroll
+    for (int j = 0; j < 15; ++j) c += (kNf4Mid[j] < left) ? 1 : 0;
+    double m = __builtin_inf();
+#pragma unroll
+    for (int j = 0; j < 15; ++j)
+        if (j == c) m = kNf4Mid[j];
+    t->mid[k] = m;
+    t->c0[k] = (uint32_t)c;
 }
 
-struct Nf4Thresholds {
-    float t[15];
+struct Nf4BlockEncoder {
+    double Md, scd;
     __device__ __forceinline__ void set(float absmax) {
-#pragma unroll
-        for (int j = 0; j < 15; ++j) t[j] = nf4_threshold(kNf4Mid[j], absmax);
+        Md = (double)(absmax > 0.f ? absmax : 1.f);
+        scd = 16.0 * __builtin_amdgcn_rcp(Md);
     }
-    // binary search over the 15 thresholds (a select tree: registers cannot be indexed)
-    __device__ __forceinline__ uint32_t encode(float w) const {
-        const bool b3 = w > t[7];
-        const float t2 = b3 ? t[11] : t[3];
-        const bool b2 = w > t2;
-        const float t1a = b2 ? t[5] : t[1];
-        const float t1b = b2 ? t[13] : t[9];
-        const bool b1 = w > (b3 ? t1b : t1a);
-        const float t0a = b1 ? t[2] : t[0];
-        const float t0b = b1 ? t[6] : t[4];
-        const float t0c = b1 ? t[10] : t[8];
-        const float t0d = b1 ? t[14] : t[12];
-        const float t0ab = b2 ? t0b : t0a;
-        const float t0cd = b2 ? t0d : t0c;
-        const bool b0 = w > (b3 ? t0cd : t0ab);
-        return (b3 ? 8u : 0u) | (b2 ? 4u : 0u) | (b1 ? 2u : 0u) | (b0 ? 1u : 0u);
+    __device__ __forceinline__ uint32_t encode(const Nf4EncTables* t, float w) const {
+        const double wd = (double)w;
+        // 1.5 * 2^52 + 16 + 16 u, rounded to an integer by the addition itself: the low word is k
+        const double xd = __builtin_fma(wd, scd, 6755399441055760.0);
+        const uint32_t k = (uint32_t)__double2loint(xd) & 63u;
+        const double th = t->mid[k] * Md;  // exact
+        return t->c0[k] + ((wd > th) ? 1u : 0u);
     }
 };
+
+// four consecutive codes -> the two code bytes they occupy (even element in the high nibble)
+__device__ __forceinline__ uint32_t nf4_pack4(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3) {
+    return ((c0 << 4) | c1) | (((c2 << 4) | c3) << 8);
+}
 
 // ---------------------------------------------------------------------------------------
 // kernel timing slots (diagnostics)

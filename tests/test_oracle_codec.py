@@ -191,3 +191,29 @@ def test_pack_layout_and_memory(cols, ld):
     full[:, 1::2] = packed & 0xF
     assert np.all(full[:, cols:] == 7)
     assert np.all(am[:, -(-cols // 64):] == 0)
+
+
+def test_decision_points_are_isolated_in_sixteenth_buckets():
+    """Geometry of the level table that a bucketed encoder may rely on (sec. 5.1): cut u = w/M into
+    buckets of width 1/16 with edges at odd multiples of 1/32.  Every bucket, widened by a guard of
+    1e-4 on both sides, holds at most one decision point (q_j + q_{j+1})/2, and no decision point
+    lies within 3e-3 of an edge; so 'code at the left edge, plus one exact comparison against the
+    next decision point' is the argmin for every element that lands in the bucket."""
+    q = [Fraction(float(v)) for v in O.NF4_LEVELS]
+    mids = [(q[j] + q[j + 1]) / 2 for j in range(15)]
+    assert min(b - a for a, b in zip(mids, mids[1:])) > Fraction(1, 16)
+    guard = Fraction(1, 10000)
+    for k in range(0, 33):
+        left, right = Fraction(2 * k - 33, 32), Fraction(2 * k - 31, 32)
+        inside = [m for m in mids if left - guard <= m <= right + guard]
+        assert len(inside) <= 1
+        for m in mids:
+            assert abs(m - left) > Fraction(3, 1000) and abs(m - right) > Fraction(3, 1000)
+    # brute force: bucket rule == argmin on a dense grid of u (M = 1), ties included
+    for num in range(-4096, 4097):
+        u = Fraction(num, 4096)
+        k = round(16 * u) + 16            # any rounding of ties works: edges are guard-banded
+        left = Fraction(2 * k - 33, 32)
+        c0 = sum(1 for m in mids if m < left - guard)
+        code = c0 + (1 if c0 < 15 and u > mids[c0] else 0)
+        assert code == sum(1 for m in mids if u > m)
