@@ -472,6 +472,31 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
         const bool light = (EPI == EPI_BF16 && K >= 2048) || EPI == EPI_FOLD;
         choice = (light && tiles(256, 256) >= 224) ? 1 : 3;
     }
+    if constexpr (EPI == EPI_BF16) {
+        // 256x256 tiles run in rounds of one tile per compute unit.  When the last round would be
+        // less than half full, the tile columns that fill whole rounds go out as one launch and the
+        // remaining columns as a second launch of 128x128 tiles, which takes about half a round.
+        const int64_t tm = (p.M + 255) / 256, tn = (p.N + 255) / 256, total = tm * tn;
+        const int64_t whole = total / 256, rest = total - whole * 256;
+        const int64_t c1 = whole * 256 / tm;  // tile columns of the first launch
+        if (g_nt_tile_override == 0 && choice == 1 && p.Nx == 0 && whole >= 2 && rest > 0 && rest < 128 &&
+            c1 > 0 && c1 < tn && (whole * 256 - c1 * tm) < 32) {
+            const int n1 = (int)c1 * 256;
+            GemmParams a = p, b = p;
+            a.N = n1;
+            for (int seg = 0; seg < 2; ++seg) {
+                if (p.A[seg].K == 0) continue;
+                a.B[seg].rows = min(p.B[seg].rows, n1);
+                b.B[seg].rows = p.B[seg].rows - n1;
+                b.B[seg].ptr = reinterpret_cast<const uint16_t*>(p.B[seg].ptr) + (BRC ? (int64_t)n1 : (int64_t)n1 * p.B[seg].ld);
+            }
+            b.N = p.N - n1;
+            b.C = reinterpret_cast<uint16_t*>(p.C) + n1;
+            hipError_t e = launch_nt<256, 256, EPI, ARC, BRC>(a, st);
+            if (e != hipSuccess) return e;
+            return launch_nt<128, 128, EPI, ARC, BRC>(b, st);
+        }
+    }
     if (choice == 1) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
     if (choice == 2) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
     return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
