@@ -18,6 +18,10 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
   merge  (Alg. 1 line 5, sec. 2.4, sec. 2.5 first paragraph):
       W_new = deq(W_q) + s * deq(P_q) @ B ;  (codes', absmax') = q_NF4(W_new)
 
+  init   (Alg. 2 lines 5-11, sec. 2.5 "Compensating for Quantization Errors"): with P
+          fixed, alternate  Q_c = q_NF4(W_hat) ;  B = P^+ (W - Q_c) / s ;
+          W_hat = W - s P B,  so that Q_c + s P B approximates W.
+
 Layout convention used by every function here ("logical" form, no padding):
   codes  : uint8 array (rows, cols), one code 0..15 per element
   absmax : float32 array (rows, ceil(cols/64)); blocks run along a row and never
@@ -35,6 +39,12 @@ notes of the repository):
   * the 16 level values are not printed in the paper (it defers to QLoRA); the
     table below is the published NF4 data type, typed in by hand, and pinned in
     the tests against its construction from normal quantiles.
+  * compensation loop (Alg. 2): the algorithm box prints B <- P^+(W_hat - Q_c), the
+    text B = P^+(Q - W); only B = P^+(W - Q_c) minimises the stated objective
+    |Q + P B - W| (a least-squares problem in B), and it is the box's own first
+    iteration (W_hat = W), so that is what every iteration computes here.  P is the
+    unquantised projection of Alg. 2 line 3 (the box uses P, not P_q, in the loop);
+    s divides B so that the layer's W_q + s P B is what approximates W.
 Parity status: every function below is pinned by tests/test_oracle_*.py against
 closed forms, brute force in rational arithmetic, library routines and
 invariants; none is "parity unpinned".
@@ -202,3 +212,37 @@ def loqt_merge_f64(Wq, Pq, B, s):
 def loqt_merge_requant(Wq, Pq, B, s):
     """W_q <- q_NF4( fp32( deq(W_q) + s deq(P_q) B ) ).  Returns (codes, absmax)."""
     return nf4_quantize(loqt_merge_f64(Wq, Pq, B, s).astype(np.float32))
+
+
+# ----------------------------------------------------------------------------
+# error-compensated initialisation of B (Alg. 2 lines 5-11, sec. 2.5)
+# ----------------------------------------------------------------------------
+def loqt_init_compensate(W, P, s, iters, B0=None):
+    """The compensation loop of Alg. 2 with P fixed.
+
+    W: (out, in) float32, the weight to be represented; P: (out, r) float32 (Alg. 2
+    line 3: the first r left singular vectors of the gradient); s: the scale of the
+    low-rank term; iters >= 1 compensation steps; B0: optional (r, in) float64 start
+    (Alg. 2 line 5 starts from B = 0).  Each step:
+        Q_c   = q_NF4(fp32(W_hat))               W_hat = W - s P B  (= W when B = 0)
+        B     = P^+ (W - deq(Q_c)) / s           least squares: argmin_B |Q_c + s P B - W|_F
+    Returns (codes, absmax) of the last Q_c, the matching B (float64) and the list of
+    objectives |deq(Q_c) + s P B - W|_F after each step.  P^+ is numpy's Moore-Penrose
+    pseudo-inverse in float64.
+    """
+    W = np.asarray(W)
+    P = np.asarray(P)
+    assert W.dtype == np.float32 and P.dtype == np.float32 and iters >= 1
+    Wd = W.astype(np.float64)
+    Pd = P.astype(np.float64)
+    Pinv = np.linalg.pinv(Pd)
+    B = np.zeros((P.shape[1], W.shape[1])) if B0 is None else np.asarray(B0, dtype=np.float64)
+    history = []
+    codes = absmax = None
+    for _ in range(iters):
+        W_hat = Wd - s * (Pd @ B)
+        codes, absmax = nf4_quantize(W_hat.astype(np.float32))
+        Q = nf4_dequantize_f64(codes, absmax)
+        B = (Pinv @ (Wd - Q)) / s
+        history.append(float(np.linalg.norm(Q + s * (Pd @ B) - Wd)))
+    return codes, absmax, B, history
