@@ -70,7 +70,7 @@ typedef struct loqt_nf4_mat {
 } loqt_nf4_mat;
 
 enum { LOQT_F32 = 0, LOQT_BF16 = 1 };                 /* output dtypes */
-enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2 };
+enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2, LOQT_OP_INIT = 3 };
 
 /* Human-readable name of a status code (static string). */
 const char *loqt_status_string(loqt_status st);
@@ -101,10 +101,12 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
  * The workspace must be 256-byte aligned; its contents are scratch.  Two calls that share a
  * workspace must be ordered on the same stream.  The figure covers both implementations (see
  * loqt_set_path), so it does not depend on the path option:
- *   FWD  : U = s x B^T (T x r bf16); pre-pass path: + bf16 copies of deq(W_q), deq(P_q)
- *   BWD  : Z = s dy deq(P_q) (T x r bf16), split-K partial sums of dB (fp32); pre-pass path:
- *          + Z^T, deq(W_q)^T, deq(P_q)^T, B^T, x^T in bf16
- *   MERGE: pre-pass path: bf16 deq(P_q) and B^T (T is ignored)
+ *   FWD  : U = s x B^T (T x r bf16); pre-pass paths: + bf16 copies of deq(W_q) (or the folded
+ *          weight) and deq(P_q)
+ *   BWD  : Z = s dy deq(P_q) (T x r bf16), fp32 slices of dB; pre-pass paths: + the same two copies
+ *   MERGE: pre-pass path: bf16 deq(P_q) (T is ignored)
+ *   INIT : loqt_init_compensate: bf16 copy of P, the residual W - deq(Q_c) in bf16, fp32 slices of
+ *          B (T is ignored)
  */
 size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r);
 
@@ -167,6 +169,34 @@ typedef struct loqt_merge_desc {
  */
 loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *descs,
                                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * loqt_init_compensate -- error-compensated initialisation of B (Alg. 2 lines 5-11; sec. 2.5
+ * "Compensating for Quantization Errors"): with the projection P fixed, find a quantised weight Q
+ * and a factor B such that Q + s P B approximates the full-precision weight W, alternating
+ *     Q_c = nf4_quantize( fl32( W - s P B ) )          (B = 0 at a cold start: Q_1 = q(W))
+ *     B   = P^+ ( W - deq(Q_c) ) / s                   (least squares: argmin_B |Q_c + s P B - W|_F)
+ * for `iters` steps (the paper uses at most five).  Of the three forms the paper prints for the
+ * B update this is the one that minimises its stated objective.  P^+ is taken as P^T: P must have
+ * orthonormal columns (Alg. 2 line 3: left singular vectors), which is a precondition, not checked.
+ *   W  : fp32 out x in,  pitch ld_w (ld_w % 4 == 0, 16-byte aligned base); read only
+ *   P  : fp32 out x r,   pitch ld_p (ld_p % 4 == 0, 16-byte aligned base); read only.  The caller
+ *        obtains P_q with nf4_quantize(P); the loop itself uses the unquantised P, as Alg. 2 does
+ *   s  : scale of the low-rank term, > 0;  iters >= 1
+ *   warm_start : 0 = start from B = 0 (Alg. 2 line 5; the contents of B are ignored);
+ *                1 = start from the B passed in
+ *   codes_out, absmax_out : out, the last Q_c in NF4 storage with pitch ld_q (ld_q % 64 == 0)
+ *   B  : bf16 r x in, pitch ld_B; in (warm start) and out (the B that matches Q_c)
+ * Products run on bf16 copies of P, B and the residual with fp32 accumulation; the quantiser is the
+ * exact one of nf4_quantize.  With iters = 1 and a cold start the codes equal nf4_quantize(W) bit
+ * for bit; later steps can differ from an exact evaluation by one level where W - s P B sits within
+ * the product's rounding error of a decision point.
+ */
+loqt_status loqt_init_compensate(const float *W, int64_t ld_w, const float *P, int64_t ld_p,
+                                 int64_t out, int64_t in, int64_t r, float s, int iters,
+                                 int warm_start, uint8_t *codes_out, float *absmax_out, int64_t ld_q,
+                                 loqt_bf16 *B, int64_t ld_B, void *ws, size_t ws_bytes,
+                                 void *hip_stream);
 
 /*
  * Implementation choice (process-wide; not thread-safe; default LOQT_PATH_AUTO).

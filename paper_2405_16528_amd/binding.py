@@ -22,7 +22,7 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 F32, BF16 = 0, 1
-OP_FWD, OP_BWD, OP_MERGE = 0, 1, 2
+OP_FWD, OP_BWD, OP_MERGE, OP_INIT = 0, 1, 2, 3
 PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
                 4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
@@ -64,6 +64,9 @@ lib.loqt_merge_requant.restype = _i
 lib.loqt_merge_requant.argtypes = [_P(NF4MatC), _vp, _vp, _P(NF4MatC), _vp, _i64, _f, _vp, _sz, _vp]
 lib.loqt_merge_requant_batched.restype = _i
 lib.loqt_merge_requant_batched.argtypes = [_i, _P(MergeDescC), _vp, _sz, _vp]
+lib.loqt_init_compensate.restype = _i
+lib.loqt_init_compensate.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _f, _i, _i, _vp, _vp, _i64, _vp, _i64,
+                                     _vp, _sz, _vp]
 lib.loqt_set_path.restype = _i
 lib.loqt_set_path.argtypes = [_i]
 lib.loqt_resolved_path.restype = _i
@@ -193,6 +196,22 @@ def loqt_merge_requant_batched(descs, ws: Optional[torch.Tensor] = None) -> None
     if ws is None:
         ws = torch.empty(merge_descs_workspace_bytes(descs), dtype=torch.uint8, device="cuda")
     _check(lib.loqt_merge_requant_batched(len(descs), descs, *_ws_args(ws), _stream()), "loqt_merge_requant_batched")
+
+
+def loqt_init_compensate(W: torch.Tensor, P: torch.Tensor, s: float, iters: int, B: torch.Tensor,
+                         warm_start: bool = False, out: Optional[NF4Tensor] = None,
+                         ws: Optional[torch.Tensor] = None) -> NF4Tensor:
+    """W: float32 (out, in), P: float32 (out, r) with orthonormal columns, B: bfloat16 (r, in), in/out.
+    Returns the quantised weight Q_c; B holds the matching factor."""
+    o, i = W.shape
+    r = P.shape[1]
+    out = out or NF4Tensor.empty(o, i, device=W.device)
+    if ws is None:
+        ws = workspace(OP_INIT, 0, o, i, r, W.device)
+    _check(lib.loqt_init_compensate(W.data_ptr(), _pitch(W), P.data_ptr(), _pitch(P), o, i, r, s, iters,
+                                    1 if warm_start else 0, out.codes.data_ptr(), out.absmax.data_ptr(), out.ld,
+                                    B.data_ptr(), _pitch(B), *_ws_args(ws), _stream()), "loqt_init_compensate")
+    return out
 
 
 def set_path(path: int) -> None:

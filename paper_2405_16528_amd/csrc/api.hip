@@ -20,7 +20,8 @@ struct TimingState {
     int created = 0;
 } g_timing;
 const char* kSlotNames[SLOT_COUNT] = {"nf4_quantize", "nf4_dequantize", "gemm_u",   "gemm_y",      "gemm_z",
-                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant", "prepass", "fold_weight"};
+                                      "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant", "prepass", "fold_weight",
+                                      "init_requant", "init_solve_b"};
 }  // namespace
 
 TimedLaunch::TimedLaunch(int slot_, hipStream_t s) : stream(s), slot(slot_), idx(-1) {
@@ -147,6 +148,26 @@ struct MergeWs {
         (void)in;
         Pb = 0;
         total = Pb + bf16_bytes(out, r);
+    }
+};
+
+// compensation loop: Pb = bf16(P) (out x r), E = W - deq(Q_c) (out x round_up(in, 64), bf16),
+// fp32 slices of B = P^T E over the contraction along `out`
+struct InitWs {
+    size_t Pb, E, partials, total;
+    int splits;
+    int64_t ldp, lde, ldr;
+    InitWs(int64_t out, int64_t in, int64_t r) {
+        ldr = (int64_t)round_up(r, 8);
+        lde = (int64_t)round_up(in, 64);
+        ldp = (int64_t)round_up(in, 4);
+        Pb = 0;
+        E = Pb + round_up((size_t)out * (size_t)ldr * 2, 256);
+        partials = E + round_up((size_t)out * (size_t)lde * 2, 256);
+        const int64_t tiles = ((r + 127) / 128) * ((in + 127) / 128);
+        const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, out / 512));
+        splits = (int)std::min(std::max<int64_t>(2, (512 + tiles / 2) / tiles), max_s);
+        total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
     }
 };
 
@@ -336,6 +357,7 @@ size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t 
             return fused > pre ? fused : pre;
         }
         case LOQT_OP_MERGE: return merge_ws_bytes(out, in, r);
+        case LOQT_OP_INIT: return InitWs(out, in, r).total;
         default: return 0;
     }
 }
@@ -580,6 +602,66 @@ int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in) {
     if (op == LOQT_OP_MERGE) return use_prepass(in) ? LOQT_PATH_PREPASS : LOQT_PATH_FUSED;
     if (!use_prepass(T)) return LOQT_PATH_FUSED;
     return use_folded(T, out, in) ? LOQT_PATH_FOLDED : LOQT_PATH_PREPASS;
+}
+
+loqt_status loqt_init_compensate(const float* W, int64_t ld_w, const float* P, int64_t ld_p, int64_t out,
+                                 int64_t in, int64_t r, float s, int iters, int warm_start, uint8_t* codes_out,
+                                 float* absmax_out, int64_t ld_q, loqt_bf16* B, int64_t ld_B, void* ws,
+                                 size_t ws_bytes, void* hip_stream) {
+    if (!W || !P || !codes_out || !absmax_out) return LOQT_INVALID_ARG;
+    if (out < 0 || in < 0 || r < 0 || ld_w < 0 || ld_p < 0 || ld_q < 0) return LOQT_INVALID_ARG;
+    if (iters < 1 || (warm_start != 0 && warm_start != 1)) return LOQT_INVALID_ARG;
+    if (!(s > 0.f) || !(s <= 3.0e38f)) return LOQT_INVALID_ARG;  // also rejects NaN
+    if (out == 0 || in == 0 || r == 0 || out > kMaxDim || in > kMaxDim || r > kMaxDim) return LOQT_BAD_SHAPE;
+    if (ld_w % 4 != 0 || ld_w < in || ld_p % 4 != 0 || ld_p < r) return LOQT_BAD_SHAPE;
+    if (ld_q % 64 != 0 || ld_q < in) return LOQT_BAD_SHAPE;
+    LOQT_TRY(check_bf16(B, r, in, ld_B));
+    if (!aligned(W, 16) || !aligned(P, 16) || !aligned(codes_out, 16) || !aligned(absmax_out, 4))
+        return LOQT_MISALIGNED;
+    if (!ws) return LOQT_INVALID_ARG;
+    if (!aligned(ws, 256)) return LOQT_MISALIGNED;
+    const InitWs L(out, in, r);
+    if (ws_bytes < L.total) return LOQT_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* base = reinterpret_cast<char*>(ws);
+    uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
+    uint16_t* E = reinterpret_cast<uint16_t*>(base + L.E);
+    float* part = reinterpret_cast<float*>(base + L.partials);
+
+    LOQT_HIP(launch_f32_to_bf16(P, out, r, ld_p, Pb, L.ldr, st));
+    GemmParams p;
+    for (int c = 0; c < iters; ++c) {
+        // Q_c = q_NF4(W - s P B) and E = W - deq(Q_c); the first step of a cold start has B = 0
+        const bool with_product = c > 0 || warm_start;
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(Pb, L.ldr, (int)out, with_product ? (int)r : 0);  // out x r, K contiguous
+        p.B[0] = bf16_operand(B, ld_B, (int)in, with_product ? (int)r : 0);     // r x in: K x rows
+        p.M = (int)out;
+        p.N = (int)ld_q;  // reach the padding columns of the code matrix
+        p.alpha = -s;
+        p.out_codes = codes_out;
+        p.out_absmax = absmax_out;
+        p.w_ld = ld_q;
+        p.w_cols = (int)in;
+        p.w_f32 = W;
+        p.w_f32_ld = ld_w;
+        p.e_out = E;
+        p.e_ld = L.lde;
+        LOQT_HIP(launch_gemm_nt(SLOT_INIT_Q, EPI_COMP, false, true, p, st));
+        // B = P^T E / s: P is out x r and E is out x in, both K x rows; contraction over `out` in slices
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(Pb, L.ldr, (int)r, (int)out);
+        p.B[0] = bf16_operand(E, L.lde, (int)in, (int)out);
+        p.M = (int)r;
+        p.N = (int)in;
+        p.alpha = 1.0f / s;
+        p.C = part;
+        p.ldc = L.ldp;
+        p.splits = L.splits;
+        LOQT_HIP(launch_gemm_nt(SLOT_INIT_B, EPI_F32_SPLITK, true, true, p, st));
+        LOQT_HIP(launch_reduce_db(part, L.splits, r, in, L.ldp, B, LOQT_BF16, ld_B, 0, st));
+    }
+    return LOQT_OK;
 }
 
 loqt_status loqt_set_path(int path) {

@@ -103,6 +103,24 @@ __global__ __launch_bounds__(256) void nf4_dequantize_kernel(const uint8_t* __re
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// fp32 -> bf16 copy of a matrix (round to nearest even): 4 elements per lane.  ld_in % 4 == 0 and
+// ld_out % 4 == 0, so a group of 4 never leaves its row's pitch; columns past `cols` are written as 0.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ in, int64_t rows, int cols,
+                                                          int64_t ld_in, uint16_t* __restrict__ out,
+                                                          int64_t ld_out) {
+    const int gpr = (cols + 3) >> 2;
+    const int64_t ngroups = rows * gpr;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < ngroups; g += (int64_t)gridDim.x * 256) {
+        const int64_t row = g / gpr;
+        const int j0 = (int)(g - row * gpr) * 4;
+        const float4 f = *reinterpret_cast<const float4*>(in + row * ld_in + j0);
+        const float v1 = j0 + 1 < cols ? f.y : 0.f, v2 = j0 + 2 < cols ? f.z : 0.f, v3 = j0 + 3 < cols ? f.w : 0.f;
+        *reinterpret_cast<uint2*>(out + row * ld_out + j0) = make_uint2(pack_bf16(f.x, v1), pack_bf16(v2, v3));
+    }
+}
+
 static int grid_for(int64_t work_items, int per_block) {
     int64_t b = (work_items + per_block - 1) / per_block;
     const int64_t cap = 256 * 64;  // enough waves to saturate HBM; the kernels grid-stride
@@ -131,6 +149,15 @@ hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t 
     else
         hipLaunchKernelGGL(nf4_dequantize_kernel<0>, dim3(grid), dim3(256), 0, st, codes, absmax, rows,
                            (int)cols, ld_q, out, ld_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_f32_to_bf16(const float* in, int64_t rows, int64_t cols, int64_t ld_in, uint16_t* out,
+                              int64_t ld_out, hipStream_t st) {
+    TimedLaunch tl(SLOT_PREPASS, st);
+    const int64_t ngroups = rows * ((cols + 3) >> 2);
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for(ngroups, 256)), dim3(256), 0, st, in, rows, (int)cols,
+                       ld_in, out, ld_out);
     return hipGetLastError();
 }
 

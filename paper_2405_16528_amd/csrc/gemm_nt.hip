@@ -363,7 +363,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         }
     } else {
         // merge (M = out, N = in): W_new = fl32(absmax * q[code]) + alpha * acc, requantised per
-        // 64-block along n.  A block of row m is 32 values in this lane and 32 in lane ^ 32.
+        // 64-block along n (Alg. 1 line 5).  A block of row m is 32 values in this lane and 32 in lane ^ 32.
+        // compensation step (Alg. 2 lines 8-10): the same with W_hat = w_f32 + alpha * acc; the residual
+        // w_f32 - deq(q(W_hat)) leaves as bf16.
         Nf4EncTables* enc = reinterpret_cast<Nf4EncTables*>(smem);
         float* lut = reinterpret_cast<float*>(smem + sizeof(Nf4EncTables));
         if (tid < 64) nf4_enc_tables_fill(enc, tid);
@@ -378,24 +380,41 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             for (int b = 0; b < TN / 2; ++b) {
                 const int nb = n0 + wn * Cfg::WTN + b * 64;  // first `in` index of the block
                 const bool live = mvalid && nb < p.w_ld;
-                float am_old = 0.f;
-                if (live) am_old = p.w_absmax[m * lda + (nb >> 6)];
-                // the 2 x 16 code bytes of the block (columns nb..nb+63 of row m); both lanes of a pair
-                // load them, this lane owns the half-words (lane >> 5) of each dword
-                uint4 cw4[2];
-                cw4[0] = cw4[1] = make_uint4(0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u);
-                if (live) {
-                    cw4[0] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1));
-                    cw4[1] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1) + 16);
-                }
                 float v[32];
+                float wsrc[EPI == EPI_COMP ? 32 : 1];
+                if constexpr (EPI == EPI_MERGE) {
+                    float am_old = 0.f;
+                    if (live) am_old = p.w_absmax[m * lda + (nb >> 6)];
+                    // the 2 x 16 code bytes of the block (columns nb..nb+63 of row m); both lanes of a pair
+                    // load them, this lane owns the half-words (lane >> 5) of each dword
+                    uint4 cw4[2];
+                    cw4[0] = cw4[1] = make_uint4(0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u);
+                    if (live) {
+                        cw4[0] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1));
+                        cw4[1] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1) + 16);
+                    }
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {  // q = 4*tt + g: tile tt of the pair, column group g
-                    const uint32_t cw = (reinterpret_cast<const uint32_t*>(&cw4[q >> 2])[q & 3] >> (16 * h)) & 0xffffu;
+                    for (int q = 0; q < 8; ++q) {  // q = 4*tt + g: tile tt of the pair, column group g
+                        const uint32_t cw =
+                            (reinterpret_cast<const uint32_t*>(&cw4[q >> 2])[q & 3] >> (16 * h)) & 0xffffu;
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        v[4 * q + j] = __builtin_fmaf(p.alpha, acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j],
-                                                      am_old * lut[nib4(cw, j)]);
+                        for (int j = 0; j < 4; ++j)
+                            v[4 * q + j] = __builtin_fmaf(p.alpha, acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j],
+                                                          am_old * lut[nib4(cw, j)]);
+                    }
+                } else {
+                    const float* wrow = p.w_f32 + (int64_t)m * p.w_f32_ld;
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
+                        float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (mvalid && nq < p.w_f32_ld) f = *reinterpret_cast<const float4*>(wrow + nq);
+                        wsrc[4 * q + 0] = f.x, wsrc[4 * q + 1] = f.y, wsrc[4 * q + 2] = f.z, wsrc[4 * q + 3] = f.w;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            v[4 * q + j] = __builtin_fmaf(p.alpha, acc[ti][2 * b + (q >> 2)][4 * (q & 3) + j],
+                                                          wsrc[4 * q + j]);
+                    }
                 }
                 if (nb + 64 > p.w_cols) {  // ragged last block (wave-uniform): columns past the end count as 0
 #pragma unroll
@@ -403,7 +422,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                         const int nq = nb + (q >> 2) * 32 + 8 * (q & 3) + 4 * h;
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
-                            if (nq + j >= p.w_cols) v[4 * q + j] = 0.f;
+                            if (nq + j >= p.w_cols) {
+                                v[4 * q + j] = 0.f;
+                                if constexpr (EPI == EPI_COMP) wsrc[4 * q + j] = 0.f;
+                            }
                     }
                 }
                 float amax = 0.f;
@@ -418,8 +440,19 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int q = 4 * tt + g;
-                        uint32_t word = nf4_pack4(be.encode(enc, v[4 * q + 0]), be.encode(enc, v[4 * q + 1]),
-                                                  be.encode(enc, v[4 * q + 2]), be.encode(enc, v[4 * q + 3]));
+                        uint32_t c[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) c[j] = be.encode(enc, v[4 * q + j]);
+                        if constexpr (EPI == EPI_COMP) {
+                            const int nq = nb + tt * 32 + 8 * g + 4 * h;
+                            float e[4];
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) e[j] = wsrc[4 * q + j] - amax * lut[c[j]];
+                            if (mvalid && nq < p.e_ld)
+                                *reinterpret_cast<uint2*>(p.e_out + (int64_t)m * p.e_ld + nq) =
+                                    make_uint2(pack_bf16(e[0], e[1]), pack_bf16(e[2], e[3]));
+                        }
+                        uint32_t word = nf4_pack4(c[0], c[1], c[2], c[3]);
                         word <<= 16 * h;                       // this lane's half of dword g
                         o[g] = word | __shfl_xor(word, 32);    // the partner lane holds the other half
                     }
@@ -466,6 +499,9 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     // or a heavy epilogue (merge, fp32 slices; measured on real data, the fold is better off with the
     // large tile) two or three resident 128x128 work-groups per
     // compute unit win: the epilogue and prologue of one overlap with the main loop of another.
+    if constexpr (EPI == EPI_COMP) {
+        return launch_nt<128, 128, EPI, ARC, BRC>(p, st);  // heavy epilogue: small tiles only
+    } else {
     int choice = g_nt_tile_override;
     if (choice == 0) {
         const int K = p.A[0].K + p.A[1].K;
@@ -500,6 +536,7 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     if (choice == 1) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
     if (choice == 2) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
     return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
+    }
 }
 
 }  // namespace
@@ -519,6 +556,7 @@ hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmPar
             case EPI_BF16: return launch_nt_sized<EPI_BF16, false, true>(p, st);
             case EPI_MERGE: return launch_nt_sized<EPI_MERGE, false, true>(p, st);
             case EPI_FOLD: return launch_nt_sized<EPI_FOLD, false, true>(p, st);
+            case EPI_COMP: return launch_nt_sized<EPI_COMP, false, true>(p, st);
             default: break;
         }
     } else if (a_rc && b_rc) {

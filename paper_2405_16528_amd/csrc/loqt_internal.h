@@ -127,6 +127,8 @@ enum KernelSlot {
     SLOT_MERGE,       // fused merge + requantise
     SLOT_PREPASS,     // NF4 -> bf16 (plain or transposed) and bf16 transposes of the large-token path
     SLOT_FOLD,        // W_eff = deq(W) + s deq(P) B in bf16 (folded path)
+    SLOT_INIT_Q,      // compensation loop: Q_c = q(W - s P B) and the residual W - deq(Q_c)
+    SLOT_INIT_B,      // compensation loop: B = P^T (W - deq(Q_c)) / s (fp32 slices)
     SLOT_COUNT
 };
 
@@ -146,6 +148,9 @@ hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t l
 hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
                              int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st,
                              int slot = SLOT_DEQUANTIZE);
+// fp32 rows x cols (pitch ld_in, 16-byte aligned rows) -> bf16 (pitch ld_out, multiple of 8), round to nearest even
+hipError_t launch_f32_to_bf16(const float* in, int64_t rows, int64_t cols, int64_t ld_in, uint16_t* out,
+                              int64_t ld_out, hipStream_t st);
 
 // operand storage kinds of the GEMM
 enum OpKind {
@@ -164,7 +169,7 @@ struct Operand {
     int K;                // extent along the contraction
 };
 
-enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3 };
+enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3, EPI_COMP = 4 };
 
 struct GemmParams {
     Operand A[2], B[2];  // up to two K segments; segment 1 unused when A[1].K == 0
@@ -188,6 +193,13 @@ struct GemmParams {
     float* out_absmax;
     int64_t w_ld;  // pitch in nibbles
     int w_cols;    // logical columns of W (= M)
+    // EPI_COMP (M = out, N = in): W_hat = w_f32 + alpha * acc is quantised into out_codes / out_absmax
+    // (pitch w_ld) and the residual w_f32 - deq(q(W_hat)) goes to e_out (bf16, pitch e_ld >= w_cols
+    // rounded up to 64)
+    const float* w_f32;
+    int64_t w_f32_ld;
+    uint16_t* e_out;
+    int64_t e_ld;
 };
 
 // which GEMM to run

@@ -24,7 +24,8 @@ def test_every_declared_symbol_is_exported(lib):
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(nf4_\w+|loqt_\w+)\s*\(", hdr))
     assert {"nf4_quantize", "nf4_dequantize", "loqt_linear_fwd", "loqt_linear_bwd", "loqt_merge_requant",
-            "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path"} <= names
+            "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path",
+            "loqt_init_compensate"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -44,6 +45,8 @@ def test_workspace_sizes(lib):
     assert fwd >= T * r * 2 + out * inp * 2 + out * r * 2
     assert bwd >= T * r * 2 + inp * out * 2 + r * out * 2 + r * inp * 4
     assert mrg >= out * r * 2
+    ini = L.loqt_workspace_bytes(L.OP_INIT, 0, out, inp, r)
+    assert ini >= out * r * 2 + out * inp * 2 + 2 * r * inp * 4 and ini % 256 == 0
     assert fwd % 256 == 0 and bwd % 256 == 0 and mrg % 256 == 0
     assert L.loqt_workspace_bytes(L.OP_FWD, 0, out, inp, r) == 0
     assert L.loqt_workspace_bytes(7, T, out, inp, r) == 0
@@ -87,3 +90,14 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.loqt_merge_requant_batched(0, None, P, ws, None) == 0                   # nothing to do
     assert lib.loqt_set_path(9) == 1
     assert lib.loqt_set_path(L.PATH_AUTO) == 0
+
+    def init(W=P, ld_w=512, Pp=P, ld_p=128, out=512, inp=512, r=128, s=1.0, iters=3, warm=0, codes=P, am=P, ld_q=512,
+             B=P, ld_B=512, w=P, wsb=ws):
+        return lib.loqt_init_compensate(W, ld_w, Pp, ld_p, out, inp, r, s, iters, warm, codes, am, ld_q, B, ld_B, w,
+                                        wsb, None)
+    assert init(W=None) == 1 and init(Pp=None) == 1 and init(codes=None) == 1 and init(B=None) == 1
+    assert init(iters=0) == 1 and init(warm=2) == 1 and init(s=0.0) == 1 and init(s=float("nan")) == 1
+    assert init(ld_w=510) == 2 and init(ld_p=126) == 2 and init(ld_q=500) == 2 and init(r=0) == 2
+    assert init(ld_B=100) == 2
+    assert init(W=P + 4) == 3 and init(w=P + 64) == 3
+    assert init(w=None) == 1 and init(wsb=1024) == 4

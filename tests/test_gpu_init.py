@@ -1,0 +1,156 @@
+"""GPU parity of loqt_init_compensate (Alg. 2 lines 5-11, sec. 2.5) against the oracle.
+
+The loop alternates a discrete step (requantise W - s P B) and a continuous one (least squares for
+B).  A single code that legitimately differs by one level (the product runs on bf16 operands) moves
+later iterates, so the steps are compared one at a time from identical inputs, and the whole loop by
+what is unique about it: the objective it reaches."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import loqt_oracle as O
+from paper_2405_16528_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(out, inp, r, seed=0):
+    rng = synth.rng_for(seed, "init-gpu", str(out), str(inp), str(r))
+    W = synth.normal_f32(rng, (out, inp), 0.02)
+    P = synth.orthonormal_f32(rng, out, r)
+    return W, P
+
+
+def _f32_dev(a, ld=None):
+    rows, cols = a.shape
+    ld = ld or (cols + 3) // 4 * 4
+    buf = np.zeros((rows, ld), dtype=np.float32)
+    buf[:, :cols] = a
+    return torch.from_numpy(buf).cuda()[:, :cols]
+
+
+def _run(W, P, s, iters, B0_bits=None, ld_q=None):
+    from tests import gpu_util as G
+    from paper_2405_16528_amd import binding as L
+    out, inp = W.shape
+    r = P.shape[1]
+    Wd, Pd = _f32_dev(W), _f32_dev(P)
+    if B0_bits is None:
+        B = G.bf16_empty(r, inp, fill=float("nan"))  # a cold start must not read it
+    else:
+        B = G.bf16_dev(B0_bits)
+    q = L.loqt_init_compensate(Wd, Pd, s, iters, B, warm_start=B0_bits is not None,
+                               out=L.NF4Tensor.empty(out, inp, ld_q))
+    torch.cuda.synchronize()
+    c, a, packed, am = G.nf4_host(q)
+    return c, a, packed, am, q.ld, G.bf16_host(B)
+
+
+@pytest.mark.parametrize("out,inp,r,s,ld_q", [(256, 512, 64, 1.0, None), (300, 333, 40, 0.25, 384),
+                                              (520, 1000, 128, 0.5, None), (64, 64, 64, 1.0, 128)])
+def test_cold_first_step(out, inp, r, s, ld_q):
+    from tests import gpu_util as G
+    W, P = _case(out, inp, r)
+    c, a, packed, am, ld, Bb = _run(W, P, s, 1, ld_q=ld_q)
+    c_ref, a_ref, B_ref, _ = O.loqt_init_compensate(W, P, s, 1)
+    assert np.array_equal(a, a_ref)
+    assert np.array_equal(c, c_ref)                       # Q_1 = q(W), bit for bit
+    p_ref, am_ref = O.pack_nf4(c_ref, a_ref, ld)          # padding nibbles 7, padding absmax 0
+    assert np.array_equal(packed, p_ref) and np.array_equal(am, am_ref)
+    err = G.max_err_over_rms(O.bf16_to_f64(Bb), B_ref)
+    print(f"init step 1 {out}x{inp} r={r}: B err/rms {err:.2e}")
+    assert err <= 2e-2
+
+
+def _requant_policy_check(c, a, W, P, B0, s):
+    """Codes of q(W - s P B0) may differ from the exact ones only where the bf16-operand product's
+    worst-case error can move the normalised value across a decision point, and then by one level."""
+    Pd = P.astype(np.float64)
+    What = W.astype(np.float64) - s * (Pd @ B0)
+    c_ref, a_ref = O.nf4_quantize(What.astype(np.float32))
+    out, inp = c_ref.shape
+    nblk = a_ref.shape[1]
+    r = Pd.shape[1]
+    E = abs(s) * (np.abs(Pd) @ np.abs(B0)) * (2.0 ** -9 + (r + 2) * 2.0 ** -24) + np.abs(What) * 2.0 ** -22
+    Emax = np.pad(E, ((0, 0), (0, nblk * 64 - inp))).reshape(out, nblk, 64).max(axis=2)
+    a64 = a_ref.astype(np.float64)
+    assert np.all(np.abs(a.astype(np.float64) - a64) <= Emax + 1e-30), "absmax outside the error bound"
+    diff = c.astype(np.int32) - c_ref.astype(np.int32)
+    bad = np.argwhere(diff != 0)
+    mids = (O.NF4_LEVELS[:-1] + O.NF4_LEVELS[1:]) * 0.5
+    for (o, i) in bad:
+        assert abs(diff[o, i]) == 1, f"code off by {diff[o, i]} at {(o, i)}"
+        am = a64[o, i // 64]
+        t = What[o, i] / am
+        mid = mids[min(c[o, i], c_ref[o, i])]
+        tol = (E[o, i] + Emax[o, i // 64]) / am * 1.01
+        assert abs(t - mid) <= tol, f"code differs at {(o, i)} though t is {abs(t - mid):.3e} from the threshold"
+    return len(bad) / c.size
+
+
+@pytest.mark.parametrize("out,inp,r,s", [(256, 512, 64, 1.0), (300, 333, 40, 0.25), (520, 1000, 128, 0.5)])
+def test_warm_step(out, inp, r, s):
+    """One step from a given B: requantisation within the policy, then B against the least-squares
+    solution for the codes the device itself produced."""
+    from tests import gpu_util as G
+    W, P = _case(out, inp, r, seed=1)
+    _, _, B1, _ = O.loqt_init_compensate(W, P, s, 1)
+    B0_bits = O.f32_to_bf16_rne(B1.astype(np.float32))
+    B0 = O.bf16_to_f64(B0_bits)
+    c, a, _, _, _, Bb = _run(W, P, s, 1, B0_bits=B0_bits)
+    rate = _requant_policy_check(c, a, W, P, B0, s)
+    print(f"init warm step {out}x{inp} r={r}: code mismatch rate {rate:.2e}")
+    assert rate <= 1e-3
+    B_ref = np.linalg.pinv(P.astype(np.float64)) @ (W.astype(np.float64) - O.nf4_dequantize_f64(c, a)) / s
+    assert G.max_err_over_rms(O.bf16_to_f64(Bb), B_ref) <= 2e-2
+
+
+def _objective(W, P, c, a, Bbits, s):
+    return float(np.linalg.norm(O.nf4_dequantize_f64(c, a) + s * (P.astype(np.float64) @ O.bf16_to_f64(Bbits))
+                                - W.astype(np.float64)))
+
+
+@pytest.mark.parametrize("out,inp,r,s", [(256, 512, 64, 1.0), (384, 640, 96, 0.5)])
+def test_whole_loop_reaches_the_oracle_objective(out, inp, r, s):
+    W, P = _case(out, inp, r, seed=2)
+    _, _, _, hist = O.loqt_init_compensate(W, P, s, 5)
+    plain = float(np.linalg.norm(O.nf4_dequantize_f64(*O.nf4_quantize(W)) - W.astype(np.float64)))
+    got = []
+    for iters in (1, 2, 3, 5):
+        c, a, _, _, _, Bb = _run(W, P, s, iters)
+        got.append(_objective(W, P, c, a, Bb, s))
+    print(f"init loop {out}x{inp} r={r}: objective device {got} oracle {hist} plain {plain:.6f}")
+    for g, h in zip(got, (hist[0], hist[1], hist[2], hist[4])):
+        assert abs(g - h) <= 5e-3 * h          # bf16 B and a handful of one-level code differences
+    assert all(b <= a * (1 + 1e-3) for a, b in zip(got, got[1:]))
+    assert got[-1] < plain
+
+
+def test_representable_weight_is_a_fixed_point():
+    rng = np.random.default_rng(3)
+    out, inp, r = 128, 256, 32
+    _, P = _case(out, inp, r, seed=3)
+    c0 = rng.integers(0, 16, size=(out, inp)).astype(np.uint8)
+    c0[:, ::64] = 15
+    a0 = np.full((out, inp // 64), 2.0 ** -6, dtype=np.float32)
+    W = O.nf4_dequantize_f32(c0, a0)
+    c, a, _, _, _, Bb = _run(W, P, 1.0, 3)
+    assert np.array_equal(c, c0) and np.array_equal(a, a0)
+    assert not np.any(Bb & 0x7FFF)  # B is +-0 everywhere
+
+
+@pytest.mark.parametrize("out,inp,r,workload", [(4096, 4096, 1024, "7b q"), (2048, 5461, 512, "1b down")])
+def test_full_size_first_step_sampled(out, inp, r, workload):
+    """Cold first step at real shapes: codes bit-exact against the oracle's quantiser, B on sampled columns
+    (column j of B depends on column j of the residual only)."""
+    W, P = _case(out, inp, r, seed=4)
+    c, a, _, _, _, Bb = _run(W, P, 1.0, 1)
+    c_ref, a_ref = O.nf4_quantize(W)
+    assert np.array_equal(a, a_ref) and np.array_equal(c, c_ref)
+    cols = synth.rng_for(4, "init-cols", workload).choice(inp, size=48, replace=False)
+    E = W[:, cols].astype(np.float64) - O.nf4_dequantize_f64(c_ref, a_ref)[:, cols]
+    B_ref = P.astype(np.float64).T @ E  # P^+ = P^T up to the fp32 rounding of an orthonormal P (1e-7)
+    got = O.bf16_to_f64(Bb)[:, cols]
+    err = float(np.abs(got - B_ref).max() / np.sqrt(np.mean(B_ref ** 2)))
+    print(f"init full size {workload}: B err/rms {err:.2e}")
+    assert err <= 2e-2
