@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the supplementary timings (codec streams, small-rank merges, the Alg. 2 loop)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain device copy of 1 GiB (reference dispatch for HBM byte counters)")
     return ap.parse_args()
@@ -77,6 +79,60 @@ def cpu_baseline(wl, seed, sample_T):
             "seconds": secs}
 
 
+def extras(L, synth, torch, wl, full_precision, layers):
+    """Supplementary timings outside the K timed steps (not part of `value`): the HBM-bound codec
+    streams, the merge at ranks where the product no longer binds, and the error-compensated
+    initialisation loop (Alg. 2), per distinct projection shape.  HIP events around 10 back-to-back calls."""
+    dev = "cuda"
+
+    def timed_us(fn, reps=10, warm=2):
+        for _ in range(warm):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    res = {"codec": [], "merge_small_rank": [], "init_compensate": []}
+    for (out, inp), (Wd, Pd) in full_precision.items():
+        n = out * inp
+        Wq = L.nf4_quantize(Wd)
+        Wb = torch.empty((out, (inp + 7) // 8 * 8), dtype=torch.bfloat16, device=dev)[:, :inp]
+        t_q = timed_us(lambda: L.nf4_quantize(Wd, out=Wq))
+        t_d = timed_us(lambda: L.nf4_dequantize(Wq, Wb))
+        res["codec"].append({"shape": f"{out}x{inp}", "quantize_us": t_q, "quantize_GBs": n * 4.5625 / t_q / 1e3,
+                             "quantize_frac_hbm": n * 4.5625 / t_q / 1e3 / PEAK_HBM_GBS,
+                             "dequantize_bf16_us": t_d, "dequantize_bf16_GBs": n * 2.5625 / t_d / 1e3,
+                             "dequantize_frac_hbm": n * 2.5625 / t_d / 1e3 / PEAK_HBM_GBS})
+        del Wb
+        Wq_out = L.NF4Tensor.empty(out, inp)
+        for r in (64, 128):
+            Pq = L.nf4_quantize(Pd[:, :r].contiguous())
+            B = (torch.randn((r, inp), device=dev, generator=gen) * 1e-3).to(torch.bfloat16)
+            ws = L.workspace(L.OP_MERGE, 0, out, inp, r)
+            t = timed_us(lambda: L.loqt_merge_requant(Wq, Pq, B, 1.0, out=Wq_out, ws=ws))
+            byts, fl = synth.bytes_merge(out, inp, r), synth.flops_merge(out, inp, r)
+            res["merge_small_rank"].append({"shape": f"{out}x{inp}", "rank": r, "us": t, "algorithmic_GBs": byts / t / 1e3,
+                                            "frac_of_hbm_peak": byts / t / 1e3 / PEAK_HBM_GBS,
+                                            "tflops": fl / t / 1e6})
+        # Alg. 2 loop, five steps from B = 0: step c costs two rank-r products of 2 out in r flop (the first
+        # step has no W - s P B product) and streams W (4 B), Q_c (0.5625 B) and the residual (2 + 2 B) per element
+        r, iters = wl.r, 5
+        B = torch.empty((r, (inp + 7) // 8 * 8), dtype=torch.bfloat16, device=dev)[:, :inp]
+        ws = L.workspace(L.OP_INIT, 0, out, inp, r)
+        t = timed_us(lambda: L.loqt_init_compensate(Wd, Pd, 1.0, iters, B, out=Wq_out, ws=ws), reps=3, warm=1)
+        fl = (2 * iters - 1) * 2.0 * out * inp * r
+        res["init_compensate"].append({"shape": f"{out}x{inp}", "rank": r, "iters": iters, "us": t,
+                                       "tflops": fl / t / 1e6, "frac_of_bf16_peak": fl / t / 1e6 / PEAK_BF16_TFLOPS})
+    return res
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -105,6 +161,7 @@ def main():
         return buf.to(torch.bfloat16)[:, :cols]
 
     layers = []
+    full_precision = {}
     ws_bytes = 256
     for (name, out, inp) in wl.projections:
         # W and P are drawn on the host by the seeded generator (P needs a QR), x / dy / B on the device
@@ -116,8 +173,11 @@ def main():
             Wp[:, :inp] = Wd
             Wd = Wp[:, :inp]
         Wq = L.nf4_quantize(Wd)
-        Pq = L.nf4_quantize(torch.from_numpy(P).to(dev))
-        del Wd
+        Pd = torch.from_numpy(P).to(dev)
+        Pq = L.nf4_quantize(Pd)
+        if not args.no_extras and (out, inp) not in full_precision:
+            full_precision[(out, inp)] = (Wd, Pd)  # one fp32 W and P per distinct shape, for the extras
+        del Wd, Pd
         lay = dict(name=name, out=out, inp=inp, Wq=Wq, Pq=Pq,
                    Wq_out=L.NF4Tensor.empty(out, inp),
                    B=randn_bf16(r, inp, 1e-3), x=randn_bf16(T, inp, 1.0), dy=randn_bf16(T, out, 1e-2),
@@ -247,6 +307,8 @@ def main():
         "kernels": kernels,
         "roofline": roofline,
     }
+    if not args.no_extras:
+        out["extras"] = extras(L, synth, torch, wl, full_precision, layers)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.seed, min(args.cpu_sample_tokens, T))
     print(json.dumps(out))
