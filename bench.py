@@ -130,6 +130,32 @@ def extras(L, synth, torch, wl, full_precision, layers):
         fl = (2 * iters - 1) * 2.0 * out * inp * r
         res["init_compensate"].append({"shape": f"{out}x{inp}", "rank": r, "iters": iters, "us": t,
                                        "tflops": fl / t / 1e6, "frac_of_bf16_peak": fl / t / 1e6 / PEAK_BF16_TFLOPS})
+    # Merge sweep over a whole 13B model (40 blocks x 7 projections, 280 distinct NF4 weights = 7.1 GB
+    # resident, far beyond the 256 MB Infinity Cache): the streaming figure of record for the merge.
+    w13 = synth.WORKLOADS["13b_block"]
+    shapes = {}
+    sweep = []
+    for (name, out, inp) in w13.projections:
+        if (out, inp) not in shapes:
+            Pq = L.nf4_quantize(torch.randn((out, w13.r), device=dev, generator=gen) / out ** 0.5)
+            B = (torch.randn((w13.r, inp), device=dev, generator=gen) * 1e-3).to(torch.bfloat16)
+            shapes[(out, inp)] = (Pq, B)
+    for _ in range(w13.n_blocks):
+        for (name, out, inp) in w13.projections:
+            W = torch.empty((out, inp), device=dev, dtype=torch.float32).normal_(0.0, 0.02, generator=gen)
+            Wq = L.nf4_quantize(W)
+            del W
+            Pq, B = shapes[(out, inp)]
+            sweep.append((Wq, None, Pq, B, 1.0))  # in place
+    descs = L.make_merge_descs(sweep)
+    ws = torch.empty(L.merge_descs_workspace_bytes(descs), dtype=torch.uint8, device=dev)
+    t = timed_us(lambda: L.loqt_merge_requant_batched(descs, ws), reps=2, warm=1)
+    byts = w13.n_blocks * sum(synth.bytes_merge(o, i, w13.r) for (_, o, i) in w13.projections)
+    fl = w13.n_blocks * sum(synth.flops_merge(o, i, w13.r) for (_, o, i) in w13.projections)
+    t_hbm, t_mfma = byts / (PEAK_HBM_GBS * 1e9) * 1e6, fl / (PEAK_BF16_TFLOPS * 1e12) * 1e6
+    res["merge_sweep_13b"] = {"layers": len(sweep), "rank": w13.r, "ms": t / 1e3, "algorithmic_GBs": byts / t / 1e3,
+                              "frac_of_hbm_peak": t_hbm / t, "tflops": fl / t / 1e6,
+                              "frac_of_binding_roof": max(t_hbm, t_mfma) / t}
     return res
 
 
