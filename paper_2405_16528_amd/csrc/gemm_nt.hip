@@ -119,7 +119,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     //  K-contiguous operand (rows x K): tile [row][64 k], slot -> row slot>>3, physical chunk slot&7,
     //    logical chunk (slot&7) ^ swz(row); rows are i*32 apart, so the chunk column is the same for all i.
     //  row-contiguous operand (K x rows): tile [64 k][BR rows], slot -> k = slot / (BR/8), physical chunk
-    //    slot % (BR/8), logical chunk physical ^ 2*(k&3); read back transposed by ds_read_b64_tr_b16.
+    //    slot % (BR/8), logical chunk physical ^ 4*(k&3); read back transposed by ds_read_b64_tr_b16.  Half a
+    //    wave of such a read touches 4 k rows x 4 chunks; a row is a multiple of 256 bytes (all 64 banks), so
+    //    the XOR has to move the four k rows to four different 64-byte groups of chunks.
     // Addresses are a wave-uniform 64-bit base (operand pointer + tile origin + K offset, scalar
     // registers) plus a 32-bit per-lane byte offset inside the tile's rows, so the loads use the
     // scalar-base form and no 64-bit address arithmetic runs on the vector unit.
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             constexpr int CPR = BR / 8;       // chunks per k row
             constexpr int KPI = 256 / CPR;    // k rows covered by one pass of the 256 threads
             const int kq = tid / CPR;         // k of chunk i is i*KPI + kq  (KPI is a multiple of 4)
-            const int logical = (tid % CPR) ^ (2 * (kq & 3));
+            const int logical = (tid % CPR) ^ (4 * (kq & 3));
             const int clast = (((O.rows - 1) >> 3) << 3) - row0;  // columns past the end: any valid chunk
             const char* sbase = reinterpret_cast<const char*>(O.ptr) + ((int64_t)k0 * O.ld + row0) * 2;
             const uint32_t off0 = (uint32_t)kq * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
@@ -207,12 +209,12 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int chunk = ((wm * Cfg::WTM + i * 32 + cb) >> 3) + (q >> 1);
-            a_rc[i] = (8 * h + jj) * (BM * 2) + ((chunk ^ (2 * jj)) << 4) + (q & 1) * 8;
+            a_rc[i] = (8 * h + jj) * (BM * 2) + ((chunk ^ (4 * jj)) << 4) + (q & 1) * 8;
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int chunk = ((wn * Cfg::WTN + j * 32 + cb) >> 3) + (q >> 1);
-            b_rc[j] = BM * ROWB + (8 * h + jj) * (BN * 2) + ((chunk ^ (2 * jj)) << 4) + (q & 1) * 8;
+            b_rc[j] = BM * ROWB + (8 * h + jj) * (BN * 2) + ((chunk ^ (4 * jj)) << 4) + (q & 1) * 8;
         }
     }
     typedef __attribute__((ext_vector_type(4))) short s16x4;
