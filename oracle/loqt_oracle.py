@@ -18,6 +18,10 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
   merge  (Alg. 1 line 5, sec. 2.4, sec. 2.5 first paragraph):
       W_new = deq(W_q) + s * deq(P_q) @ B ;  (codes', absmax') = q_NF4(W_new)
 
+  right  (sec. 2.2 first paragraph: "we compute P^T G if m <= n and G Q otherwise ... if
+          m > n the same reasoning holds for Q^T"): the projection sits on the input side,
+      W_eff = deq(W_q) + s * Bp @ deq(Q_q)^T   Q in x r fixed (NF4), Bp out x r trainable;
+      y = x @ W_eff^T ; dx = dy @ W_eff ; dBp = s * dy^T @ (x @ deq(Q_q))
   init   (Alg. 2 lines 5-11, sec. 2.5 "Compensating for Quantization Errors"): with P
           fixed, alternate  Q_c = q_NF4(W_hat) ;  B = P^+ (W - Q_c) / s ;
           W_hat = W - s P B,  so that Q_c + s P B approximates W.
@@ -212,6 +216,39 @@ def loqt_merge_f64(Wq, Pq, B, s):
 def loqt_merge_requant(Wq, Pq, B, s):
     """W_q <- q_NF4( fp32( deq(W_q) + s deq(P_q) B ) ).  Returns (codes, absmax)."""
     return nf4_quantize(loqt_merge_f64(Wq, Pq, B, s).astype(np.float32))
+
+
+# ----------------------------------------------------------------------------
+# right-side projection variant (sec. 2.2: one-sided projection G Q when m > n)
+# ----------------------------------------------------------------------------
+def loqt_right_weff_f64(Wq, Qq, Bp, s):
+    """deq(W_q) + s Bp deq(Q_q)^T in float64.  Wq of (out, in), Qq of (in, r), Bp (out, r) bf16 bits."""
+    return nf4_dequantize_f64(*Wq) + s * (bf16_to_f64(Bp) @ nf4_dequantize_f64(*Qq).T)
+
+
+def loqt_linear_fwd_right(x, Wq, Qq, Bp, s):
+    """y = x deq(W_q)^T + s (x deq(Q_q)) Bp^T   (float64); x (T, in) bf16 bits."""
+    xd = bf16_to_f64(x)
+    V = xd @ nf4_dequantize_f64(*Qq)
+    return xd @ nf4_dequantize_f64(*Wq).T + s * (V @ bf16_to_f64(Bp).T)
+
+
+def loqt_linear_bwd_right(dy, x, Wq, Qq, Bp, s):
+    """dx = dy deq(W_q) + s (dy Bp) deq(Q_q)^T ;  dBp = s dy^T (x deq(Q_q))   (float64).
+
+    The weight gradient goes to Bp alone: G^Bp = G^W Q, the right-sided projection of sec. 2.2.
+    """
+    dyd = bf16_to_f64(dy)
+    xd = bf16_to_f64(x)
+    Qd = nf4_dequantize_f64(*Qq)
+    dx = dyd @ nf4_dequantize_f64(*Wq) + s * ((dyd @ bf16_to_f64(Bp)) @ Qd.T)
+    dBp = s * (dyd.T @ (xd @ Qd))
+    return dx, dBp
+
+
+def loqt_merge_requant_right(Wq, Qq, Bp, s):
+    """W_q <- q_NF4( fp32( deq(W_q) + s Bp deq(Q_q)^T ) )  (Alg. 1 line 5 for the right-side form)."""
+    return nf4_quantize(loqt_right_weff_f64(Wq, Qq, Bp, s).astype(np.float32))
 
 
 # ----------------------------------------------------------------------------
