@@ -70,7 +70,8 @@ typedef struct loqt_nf4_mat {
 } loqt_nf4_mat;
 
 enum { LOQT_F32 = 0, LOQT_BF16 = 1 };                 /* output dtypes */
-enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2, LOQT_OP_INIT = 3 };
+enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2, LOQT_OP_INIT = 3,
+       LOQT_OP_FWD_RIGHT = 4, LOQT_OP_BWD_RIGHT = 5, LOQT_OP_MERGE_RIGHT = 6 };
 
 /* Human-readable name of a status code (static string). */
 const char *loqt_status_string(loqt_status st);
@@ -107,6 +108,9 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
  *   MERGE: pre-pass path: bf16 deq(P_q) (T is ignored)
  *   INIT : loqt_init_compensate: bf16 copy of P, the residual W - deq(Q_c) in bf16, fp32 slices of
  *          B (T is ignored)
+ *   FWD_RIGHT, BWD_RIGHT, MERGE_RIGHT: the right-side variant below, with r = columns of Q_q:
+ *          bf16 deq(Q_q); forward and backward + the folded weight (out x in bf16); backward +
+ *          V = s x deq(Q_q) (T x r bf16) and fp32 slices of dBp
  */
 size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r);
 
@@ -169,6 +173,36 @@ typedef struct loqt_merge_desc {
  */
 loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *descs,
                                        void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Right-side projection variant (sec. 2.2: the one-sided projection is P^T G when the weight has
+ * no more rows than columns and G Q otherwise; "if m > n the same reasoning holds for Q^T").  The
+ * fixed NF4 projection sits on the input side and the trainable 16-bit factor on the output side:
+ *     W_eff = deq(Wq) + s * Bp deq(Qq)^T        Wq: out x in,  Qq: in x r,  Bp: out x r (pitch ld_Bp)
+ *   loqt_linear_fwd_right    y  = x W_eff^T  = x deq(Wq)^T + s (x deq(Qq)) Bp^T
+ *   loqt_linear_bwd_right    dx = dy W_eff   = dy deq(Wq) + s (dy Bp) deq(Qq)^T      (dx may be NULL)
+ *                            dBp (out x r, LOQT_F32 or LOQT_BF16, pitch ld_dBp >= r, optional +=)
+ *                                = s dy^T (x deq(Qq))       (G^Bp = G^W Q; no full dW is formed)
+ *   loqt_merge_requant_right W_q <- nf4_quantize( deq(Wq) + s Bp deq(Qq)^T ), aliasing rules of
+ *                            loqt_merge_requant; Bp is not modified
+ * Arguments, tolerances and error behaviour are those of the left-side calls above.  One
+ * implementation for every size: deq(Qq) is expanded to bf16 and the rank-r term is folded into a
+ * bf16 copy of the weight once per call (2 out in r flop), then y and dx are single products.
+ */
+loqt_status loqt_linear_fwd_right(const loqt_bf16 *x, int64_t ld_x, int64_t T,
+                                  const loqt_nf4_mat *Wq, const loqt_nf4_mat *Qq,
+                                  const loqt_bf16 *Bp, int64_t ld_Bp, float s,
+                                  loqt_bf16 *y, int64_t ld_y,
+                                  void *ws, size_t ws_bytes, void *hip_stream);
+loqt_status loqt_linear_bwd_right(const loqt_bf16 *dy, int64_t ld_dy, const loqt_bf16 *x, int64_t ld_x,
+                                  int64_t T, const loqt_nf4_mat *Wq, const loqt_nf4_mat *Qq,
+                                  const loqt_bf16 *Bp, int64_t ld_Bp, float s,
+                                  loqt_bf16 *dx, int64_t ld_dx,
+                                  void *dBp, int dBp_dtype, int64_t ld_dBp, int accumulate,
+                                  void *ws, size_t ws_bytes, void *hip_stream);
+loqt_status loqt_merge_requant_right(const loqt_nf4_mat *Wq, uint8_t *codes_out, float *absmax_out,
+                                     const loqt_nf4_mat *Qq, const loqt_bf16 *Bp, int64_t ld_Bp,
+                                     float s, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * loqt_init_compensate -- error-compensated initialisation of B (Alg. 2 lines 5-11; sec. 2.5

@@ -22,7 +22,7 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 F32, BF16 = 0, 1
-OP_FWD, OP_BWD, OP_MERGE, OP_INIT = 0, 1, 2, 3
+OP_FWD, OP_BWD, OP_MERGE, OP_INIT, OP_FWD_RIGHT, OP_BWD_RIGHT, OP_MERGE_RIGHT = 0, 1, 2, 3, 4, 5, 6
 PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
                 4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
@@ -64,6 +64,12 @@ lib.loqt_merge_requant.restype = _i
 lib.loqt_merge_requant.argtypes = [_P(NF4MatC), _vp, _vp, _P(NF4MatC), _vp, _i64, _f, _vp, _sz, _vp]
 lib.loqt_merge_requant_batched.restype = _i
 lib.loqt_merge_requant_batched.argtypes = [_i, _P(MergeDescC), _vp, _sz, _vp]
+lib.loqt_linear_fwd_right.restype = _i
+lib.loqt_linear_fwd_right.argtypes = lib.loqt_linear_fwd.argtypes
+lib.loqt_linear_bwd_right.restype = _i
+lib.loqt_linear_bwd_right.argtypes = lib.loqt_linear_bwd.argtypes
+lib.loqt_merge_requant_right.restype = _i
+lib.loqt_merge_requant_right.argtypes = lib.loqt_merge_requant.argtypes
 lib.loqt_init_compensate.restype = _i
 lib.loqt_init_compensate.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _f, _i, _i, _vp, _vp, _i64, _vp, _i64,
                                      _vp, _sz, _vp]
@@ -196,6 +202,35 @@ def loqt_merge_requant_batched(descs, ws: Optional[torch.Tensor] = None) -> None
     if ws is None:
         ws = torch.empty(merge_descs_workspace_bytes(descs), dtype=torch.uint8, device="cuda")
     _check(lib.loqt_merge_requant_batched(len(descs), descs, *_ws_args(ws), _stream()), "loqt_merge_requant_batched")
+
+
+def loqt_linear_fwd_right(x, Wq: NF4Tensor, Qq: NF4Tensor, Bp, s: float, y, ws) -> torch.Tensor:
+    """Right-side variant: Wq (out, in), Qq (in, r), Bp bfloat16 (out, r)."""
+    _check(lib.loqt_linear_fwd_right(x.data_ptr(), _pitch(x), x.shape[0], C.byref(Wq.c()), C.byref(Qq.c()),
+                                     Bp.data_ptr(), _pitch(Bp), s, y.data_ptr(), _pitch(y), *_ws_args(ws),
+                                     _stream()), "loqt_linear_fwd_right")
+    return y
+
+
+def loqt_linear_bwd_right(dy, x, Wq: NF4Tensor, Qq: NF4Tensor, Bp, s: float, dx, dBp, accumulate: bool, ws):
+    """dx may be None; dBp float32 or bfloat16 (out, r)."""
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[dBp.dtype]
+    _check(lib.loqt_linear_bwd_right(dy.data_ptr(), _pitch(dy), x.data_ptr(), _pitch(x), x.shape[0],
+                                     C.byref(Wq.c()), C.byref(Qq.c()), Bp.data_ptr(), _pitch(Bp), s,
+                                     _ptr(dx), _pitch(dx) if dx is not None else 0, dBp.data_ptr(), dt, _pitch(dBp),
+                                     1 if accumulate else 0, *_ws_args(ws), _stream()), "loqt_linear_bwd_right")
+    return dx, dBp
+
+
+def loqt_merge_requant_right(Wq: NF4Tensor, Qq: NF4Tensor, Bp, s: float, out: Optional[NF4Tensor] = None,
+                             ws: Optional[torch.Tensor] = None) -> NF4Tensor:
+    out = out or Wq
+    if ws is None:
+        ws = workspace(OP_MERGE_RIGHT, 0, Wq.rows, Wq.cols, Qq.cols, Wq.codes.device)
+    _check(lib.loqt_merge_requant_right(C.byref(Wq.c()), out.codes.data_ptr(), out.absmax.data_ptr(),
+                                        C.byref(Qq.c()), Bp.data_ptr(), _pitch(Bp), s, *_ws_args(ws), _stream()),
+           "loqt_merge_requant_right")
+    return out
 
 
 def loqt_init_compensate(W: torch.Tensor, P: torch.Tensor, s: float, iters: int, B: torch.Tensor,

@@ -171,6 +171,40 @@ struct InitWs {
     }
 };
 
+// right-side variant (W + s Bp Q^T): Qb = deq(Q) (in x r), We = folded weight (out x in), V = s x Qb
+// (T x r), fp32 slices of dBp = dy^T V over the contraction along T
+struct RightWs {
+    size_t Qb, We, V, partials, total;
+    int splits;
+    int64_t ldr, ldw, ldp;
+    RightWs(int op, int64_t T, int64_t out, int64_t in, int64_t r) {
+        ldr = (int64_t)round_up(r, 8);
+        ldw = (int64_t)round_up(in, 8);
+        ldp = (int64_t)round_up(r, 4);
+        splits = 1;
+        Qb = 0;
+        We = Qb + bf16_bytes(in, r);
+        V = We + (op == LOQT_OP_MERGE_RIGHT ? 0 : bf16_bytes(out, in));
+        partials = V + (op == LOQT_OP_BWD_RIGHT ? bf16_bytes(T, r) : 0);
+        total = partials;
+        if (op == LOQT_OP_BWD_RIGHT) {
+            const int64_t tiles = ((out + 127) / 128) * ((r + 127) / 128);
+            const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, T / 512));
+            splits = (int)std::min(std::max<int64_t>(2, (512 + tiles / 2) / tiles), max_s);
+            total = partials + round_up((size_t)splits * (size_t)out * (size_t)ldp * 4, 256);
+        }
+    }
+};
+
+// shapes of the right-side layer: W out x in, Q in x r, Bp out x r
+loqt_status check_layer_right(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Qq, const void* Bp, int64_t ld_Bp) {
+    LOQT_TRY(check_nf4(Wq));
+    LOQT_TRY(check_nf4(Qq));
+    if (Qq->rows != Wq->cols) return LOQT_BAD_SHAPE;
+    LOQT_TRY(check_bf16(Bp, Wq->rows, Qq->cols, ld_Bp));
+    return LOQT_OK;
+}
+
 Operand nf4_operand(const loqt_nf4_mat* m, int rows, int K) {
     Operand o;
     o.ptr = m->codes;
@@ -283,12 +317,8 @@ loqt_status check_merge_ws(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, void*
     return LOQT_OK;
 }
 
-loqt_status check_merge(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
-                        const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B) {
-    if (!codes_out || !absmax_out) return LOQT_INVALID_ARG;
-    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
-    if (!aligned(codes_out, 16) || !aligned(absmax_out, 4)) return LOQT_MISALIGNED;
-    // full aliasing is allowed, partial overlap is not
+// full aliasing of the merge output with its input is allowed, partial overlap is not
+loqt_status check_out_alias(const loqt_nf4_mat* Wq, const uint8_t* codes_out, const float* absmax_out) {
     const size_t cb = (size_t)Wq->rows * (size_t)(Wq->ld / 2), ab = (size_t)Wq->rows * (size_t)(Wq->ld / 64) * 4;
     const uint8_t* ci = Wq->codes;
     const uint8_t* ai = reinterpret_cast<const uint8_t*>(Wq->absmax);
@@ -296,6 +326,14 @@ loqt_status check_merge(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absma
     if (codes_out != ci && codes_out < ci + cb && ci < codes_out + cb) return LOQT_INVALID_ARG;
     if (ao != ai && ao < ai + ab && ai < ao + ab) return LOQT_INVALID_ARG;
     return LOQT_OK;
+}
+
+loqt_status check_merge(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                        const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B) {
+    if (!codes_out || !absmax_out) return LOQT_INVALID_ARG;
+    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
+    if (!aligned(codes_out, 16) || !aligned(absmax_out, 4)) return LOQT_MISALIGNED;
+    return check_out_alias(Wq, codes_out, absmax_out);
 }
 
 }  // namespace
@@ -358,6 +396,11 @@ size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t 
         }
         case LOQT_OP_MERGE: return merge_ws_bytes(out, in, r);
         case LOQT_OP_INIT: return InitWs(out, in, r).total;
+        case LOQT_OP_FWD_RIGHT:
+        case LOQT_OP_BWD_RIGHT:
+            if (T <= 0) return 0;
+            return RightWs(op, T, out, in, r).total;
+        case LOQT_OP_MERGE_RIGHT: return RightWs(op, 0, out, in, r).total;
         default: return 0;
     }
 }
@@ -661,6 +704,157 @@ loqt_status loqt_init_compensate(const float* W, int64_t ld_w, const float* P, i
         LOQT_HIP(launch_gemm_nt(SLOT_INIT_B, EPI_F32_SPLITK, true, true, p, st));
         LOQT_HIP(launch_reduce_db(part, L.splits, r, in, L.ldp, B, LOQT_BF16, ld_B, 0, st));
     }
+    return LOQT_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// right-side projection variant: W_eff = deq(W_q) + s Bp deq(Q_q)^T
+// ---------------------------------------------------------------------------------------
+namespace {
+// Qb = deq(Qq) (bf16, in x r) and We = deq(Wq) + s Bp Qb^T (bf16, out x in, pitch ldw)
+loqt_status fold_weight_right(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Qq, const loqt_bf16* Bp, int64_t ld_Bp,
+                              float s, uint16_t* Qb, int64_t ldr, uint16_t* We, int64_t ldw, hipStream_t st) {
+    const int64_t out = Wq->rows, in = Wq->cols, r = Qq->cols;
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(Bp, ld_Bp, (int)out, (int)r);  // out x r, K contiguous
+    p.B[0] = bf16_operand(Qb, ldr, (int)in, (int)r);     // in x r: rows x K, K contiguous
+    p.M = (int)out;
+    p.N = (int)in;
+    p.alpha = s;
+    p.C = We;
+    p.ldc = ldw;
+    p.w_codes = Wq->codes;
+    p.w_absmax = Wq->absmax;
+    p.w_ld = Wq->ld;
+    p.w_cols = (int)in;
+    LOQT_HIP(launch_gemm_nt(SLOT_FOLD, EPI_FOLD, false, false, p, st));
+    return LOQT_OK;
+}
+loqt_status check_ws(void* ws, size_t ws_bytes, size_t need) {
+    if (!ws) return LOQT_INVALID_ARG;
+    if (!aligned(ws, 256)) return LOQT_MISALIGNED;
+    if (ws_bytes < need) return LOQT_WORKSPACE_TOO_SMALL;
+    return LOQT_OK;
+}
+}  // namespace
+
+loqt_status loqt_linear_fwd_right(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_nf4_mat* Wq,
+                                  const loqt_nf4_mat* Qq, const loqt_bf16* Bp, int64_t ld_Bp, float s,
+                                  loqt_bf16* y, int64_t ld_y, void* ws, size_t ws_bytes, void* hip_stream) {
+    LOQT_TRY(check_layer_right(Wq, Qq, Bp, ld_Bp));
+    const int64_t out = Wq->rows, in = Wq->cols, r = Qq->cols;
+    LOQT_TRY(check_bf16(x, T, in, ld_x));
+    LOQT_TRY(check_bf16(y, T, out, ld_y));
+    const RightWs L(LOQT_OP_FWD_RIGHT, T, out, in, r);
+    LOQT_TRY(check_ws(ws, ws_bytes, L.total));
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* base = reinterpret_cast<char*>(ws);
+    uint16_t* Qb = reinterpret_cast<uint16_t*>(base + L.Qb);
+    uint16_t* We = reinterpret_cast<uint16_t*>(base + L.We);
+    LOQT_HIP(launch_dequantize(Qq->codes, Qq->absmax, in, r, Qq->ld, Qb, LOQT_BF16, L.ldr, st, SLOT_PREPASS));
+    LOQT_TRY(fold_weight_right(Wq, Qq, Bp, ld_Bp, s, Qb, L.ldr, We, L.ldw, st));
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+    p.B[0] = bf16_operand(We, L.ldw, (int)out, (int)in);
+    p.M = (int)T;
+    p.N = (int)out;
+    p.alpha = 1.0f;
+    p.C = y;
+    p.ldc = ld_y;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, false, false, p, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_linear_bwd_right(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
+                                  const loqt_nf4_mat* Wq, const loqt_nf4_mat* Qq, const loqt_bf16* Bp,
+                                  int64_t ld_Bp, float s, loqt_bf16* dx, int64_t ld_dx, void* dBp, int dBp_dtype,
+                                  int64_t ld_dBp, int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+    LOQT_TRY(check_layer_right(Wq, Qq, Bp, ld_Bp));
+    const int64_t out = Wq->rows, in = Wq->cols, r = Qq->cols;
+    LOQT_TRY(check_bf16(dy, T, out, ld_dy));
+    LOQT_TRY(check_bf16(x, T, in, ld_x));
+    if (dx) LOQT_TRY(check_bf16(dx, T, in, ld_dx));
+    if (!dBp) return LOQT_INVALID_ARG;
+    if (dBp_dtype != LOQT_F32 && dBp_dtype != LOQT_BF16) return LOQT_INVALID_ARG;
+    if (ld_dBp < r) return LOQT_BAD_SHAPE;
+    if (!aligned(dBp, dBp_dtype == LOQT_BF16 ? 2 : 4)) return LOQT_MISALIGNED;
+    const RightWs L(LOQT_OP_BWD_RIGHT, T, out, in, r);
+    LOQT_TRY(check_ws(ws, ws_bytes, L.total));
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* base = reinterpret_cast<char*>(ws);
+    uint16_t* Qb = reinterpret_cast<uint16_t*>(base + L.Qb);
+    uint16_t* We = reinterpret_cast<uint16_t*>(base + L.We);
+    uint16_t* V = reinterpret_cast<uint16_t*>(base + L.V);
+    float* part = reinterpret_cast<float*>(base + L.partials);
+    LOQT_HIP(launch_dequantize(Qq->codes, Qq->absmax, in, r, Qq->ld, Qb, LOQT_BF16, L.ldr, st, SLOT_PREPASS));
+    GemmParams p;
+    // V = s x deq(Q): deq(Q) is in x r, i.e. K x rows
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+    p.B[0] = bf16_operand(Qb, L.ldr, (int)r, (int)in);
+    p.M = (int)T;
+    p.N = (int)r;
+    p.alpha = s;
+    p.C = V;
+    p.ldc = L.ldr;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_U, EPI_BF16, false, true, p, st));
+    if (dx) {
+        // dx = dy W_eff, W_eff out x in: K x rows
+        LOQT_TRY(fold_weight_right(Wq, Qq, Bp, ld_Bp, s, Qb, L.ldr, We, L.ldw, st));
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+        p.B[0] = bf16_operand(We, L.ldw, (int)in, (int)out);
+        p.M = (int)T;
+        p.N = (int)in;
+        p.alpha = 1.0f;
+        p.C = dx;
+        p.ldc = ld_dx;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, false, true, p, st));
+    }
+    // dBp = dy^T V: dy is T x out and V is T x r, both K x rows; contraction over T in slices
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(dy, ld_dy, (int)out, (int)T);
+    p.B[0] = bf16_operand(V, L.ldr, (int)r, (int)T);
+    p.M = (int)out;
+    p.N = (int)r;
+    p.alpha = 1.0f;
+    p.C = part;
+    p.ldc = L.ldp;
+    p.splits = L.splits;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DB, EPI_F32_SPLITK, true, true, p, st));
+    LOQT_HIP(launch_reduce_db(part, L.splits, out, r, L.ldp, dBp, dBp_dtype, ld_dBp, accumulate, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_merge_requant_right(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,
+                                     const loqt_nf4_mat* Qq, const loqt_bf16* Bp, int64_t ld_Bp, float s, void* ws,
+                                     size_t ws_bytes, void* hip_stream) {
+    if (!codes_out || !absmax_out) return LOQT_INVALID_ARG;
+    LOQT_TRY(check_layer_right(Wq, Qq, Bp, ld_Bp));
+    if (!aligned(codes_out, 16) || !aligned(absmax_out, 4)) return LOQT_MISALIGNED;
+    LOQT_TRY(check_out_alias(Wq, codes_out, absmax_out));
+    const int64_t out = Wq->rows, in = Wq->cols, r = Qq->cols;
+    const RightWs L(LOQT_OP_MERGE_RIGHT, 0, out, in, r);
+    LOQT_TRY(check_ws(ws, ws_bytes, L.total));
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint16_t* Qb = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(ws) + L.Qb);
+    LOQT_HIP(launch_dequantize(Qq->codes, Qq->absmax, in, r, Qq->ld, Qb, LOQT_BF16, L.ldr, st, SLOT_PREPASS));
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(Bp, ld_Bp, (int)out, (int)r);  // rows of the tile are rows of W
+    p.B[0] = bf16_operand(Qb, L.ldr, (int)in, (int)r);   // in x r: columns of the tile run along `in`
+    p.M = (int)out;
+    p.N = (int)Wq->ld;  // reach the padding columns (operand rows past `in` are never used)
+    p.alpha = s;
+    p.w_codes = Wq->codes;
+    p.w_absmax = Wq->absmax;
+    p.out_codes = codes_out;
+    p.out_absmax = absmax_out;
+    p.w_ld = Wq->ld;
+    p.w_cols = (int)in;
+    LOQT_HIP(launch_gemm_nt(SLOT_MERGE, EPI_MERGE, false, false, p, st));
     return LOQT_OK;
 }
 

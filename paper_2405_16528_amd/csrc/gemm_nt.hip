@@ -129,6 +129,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         constexpr bool RC = decltype(rc_tag)::value;
         constexpr int BR = decltype(br_tag)::value;
         constexpr int NC = BR / 32;  // chunks per thread
+        // a tile that lies wholly past the operand's last row (the merge walks the padding columns of the
+        // code matrix, which can exceed `in` by more than a tile) reads the operand's first rows instead:
+        // its products are never used, and the clamps below then never go negative
+        if (row0 >= O.rows) row0 = 0;
         const int kleft = O.K - k0;
         const uint32_t ld2 = (uint32_t)O.ld * 2u;  // row pitch in bytes (a tile spans < 2^32 bytes)
         if constexpr (!RC) {
@@ -551,6 +555,8 @@ hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmPar
     if (!a_rc && !b_rc) {
         switch (epi) {
             case EPI_BF16: return launch_nt_sized<EPI_BF16, false, false>(p, st);
+            case EPI_MERGE: return launch_nt_sized<EPI_MERGE, false, false>(p, st);
+            case EPI_FOLD: return launch_nt_sized<EPI_FOLD, false, false>(p, st);
             default: break;
         }
     } else if (!a_rc && b_rc) {

@@ -25,7 +25,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = set(re.findall(r"\b(nf4_\w+|loqt_\w+)\s*\(", hdr))
     assert {"nf4_quantize", "nf4_dequantize", "loqt_linear_fwd", "loqt_linear_bwd", "loqt_merge_requant",
             "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path",
-            "loqt_init_compensate"} <= names
+            "loqt_init_compensate", "loqt_linear_fwd_right", "loqt_linear_bwd_right",
+            "loqt_merge_requant_right"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -45,6 +46,11 @@ def test_workspace_sizes(lib):
     assert fwd >= T * r * 2 + out * inp * 2 + out * r * 2
     assert bwd >= T * r * 2 + inp * out * 2 + r * out * 2 + r * inp * 4
     assert mrg >= out * r * 2
+    fr = L.loqt_workspace_bytes(L.OP_FWD_RIGHT, T, out, inp, r)
+    br = L.loqt_workspace_bytes(L.OP_BWD_RIGHT, T, out, inp, r)
+    mr = L.loqt_workspace_bytes(L.OP_MERGE_RIGHT, 0, out, inp, r)
+    assert fr >= inp * r * 2 + out * inp * 2 and br >= fr + T * r * 2 + 2 * out * r * 4 and mr >= inp * r * 2
+    assert fr % 256 == 0 and br % 256 == 0 and mr % 256 == 0
     ini = L.loqt_workspace_bytes(L.OP_INIT, 0, out, inp, r)
     assert ini >= out * r * 2 + out * inp * 2 + 2 * r * inp * 4 and ini % 256 == 0
     assert fwd % 256 == 0 and bwd % 256 == 0 and mrg % 256 == 0
@@ -90,6 +96,20 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.loqt_merge_requant_batched(0, None, P, ws, None) == 0                   # nothing to do
     assert lib.loqt_set_path(9) == 1
     assert lib.loqt_set_path(L.PATH_AUTO) == 0
+
+    Qm = L.NF4MatC(P, P, 512, 128, 128)   # in x r
+    Qbad = L.NF4MatC(P, P, 256, 128, 128)  # rows differ from W's columns
+    assert lib.loqt_linear_fwd_right(P, 512, 256, C.byref(W), C.byref(Qbad), P, 128, 1.0, P, 512, P, ws, None) == 2
+    assert lib.loqt_linear_fwd_right(P, 512, 256, C.byref(W), C.byref(Qm), P, 100, 1.0, P, 512, P, ws, None) == 2
+    assert lib.loqt_linear_fwd_right(P, 512, 256, C.byref(W), C.byref(Qm), P, 128, 1.0, P, 512, P, 16, None) == 4
+    assert lib.loqt_linear_fwd_right(P, 512, 256, C.byref(W), None, P, 128, 1.0, P, 512, P, ws, None) == 1
+    assert lib.loqt_linear_bwd_right(P, 512, P, 512, 256, C.byref(W), C.byref(Qm), P, 128, 1.0, P, 512, None, 0, 128,
+                                     0, P, ws, None) == 1                              # dBp missing
+    assert lib.loqt_linear_bwd_right(P, 512, P, 512, 256, C.byref(W), C.byref(Qm), P, 128, 1.0, P, 512, P, 0, 100,
+                                     0, P, ws, None) == 2                              # ld_dBp < r
+    assert lib.loqt_merge_requant_right(C.byref(W), None, P, C.byref(Qm), P, 128, 1.0, P, ws, None) == 1
+    assert lib.loqt_merge_requant_right(C.byref(W), P + 64, P, C.byref(Qm), P, 128, 1.0, P, ws, None) == 1
+    assert lib.loqt_merge_requant_right(C.byref(W), P, P, C.byref(Qm), P, 128, 1.0, None, ws, None) == 1
 
     def init(W=P, ld_w=512, Pp=P, ld_p=128, out=512, inp=512, r=128, s=1.0, iters=3, warm=0, codes=P, am=P, ld_q=512,
              B=P, ld_B=512, w=P, wsb=ws):

@@ -47,7 +47,8 @@ def _run(W, P, s, iters, B0_bits=None, ld_q=None):
 
 
 @pytest.mark.parametrize("out,inp,r,s,ld_q", [(256, 512, 64, 1.0, None), (300, 333, 40, 0.25, 384),
-                                              (520, 1000, 128, 0.5, None), (64, 64, 64, 1.0, 128)])
+                                              (520, 1000, 128, 0.5, None), (64, 64, 64, 1.0, 128),
+                                              (130, 200, 40, 1.0, 512)])
 def test_cold_first_step(out, inp, r, s, ld_q):
     from tests import gpu_util as G
     W, P = _case(out, inp, r)

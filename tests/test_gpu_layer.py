@@ -139,7 +139,8 @@ def _merge_policy_check(c, a, Wq, Pq, B, s):
 
 
 @pytest.mark.parametrize("out,inp,r,ld", [(512, 512, 128, None), (300, 456, 64, 512), (1100, 333, 192, None),
-                                          (260, 2048, 256, None)])
+                                          (260, 2048, 256, None),
+                                          (300, 200, 64, 512)])  # pitch exceeds `in` by more than two tiles
 def test_merge_parity(out, inp, r, ld):
     from tests import gpu_util as G
     from paper_2405_16528_amd import binding as L
