@@ -26,6 +26,9 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
           fixed, alternate  Q_c = q_NF4(W_hat) ;  B = P^+ (W - Q_c) / s ;
           W_hat = W - s P B,  so that Q_c + s P B approximates W.
 
+  step   (Alg. 1 line 9: B_{t+1} = B_t - rho(G^B_t), rho = Adam; sec. 2.5 last paragraph and
+          the hyper-parameter appendix: W is updated at steps T_i whose gaps are tau + psi^i).
+
 Layout convention used by every function here ("logical" form, no padding):
   codes  : uint8 array (rows, cols), one code 0..15 per element
   absmax : float32 array (rows, ceil(cols/64)); blocks run along a row and never
@@ -49,6 +52,12 @@ notes of the repository):
     iteration (W_hat = W), so that is what every iteration computes here.  P is the
     unquantised projection of Alg. 2 line 3 (the box uses P, not P_q, in the loop);
     s divides B so that the layer's W_q + s P B is what approximates W.
+  * Adam (the paper only names it): the published algorithm with bias correction,
+    m = b1 m + (1-b1) g, v = b2 v + (1-b2) g^2, B -= lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps);
+    no weight decay; pinned against torch.optim.Adam.
+  * update schedule: the text gives T_i = tau + psi^i once as the steps themselves and once
+    (appendix, and the ablation's "starting at 100 ... up to 2500") as growing intervals; intervals
+    are the reading taken: gap_i = min(cap, floor(tau + psi^i)), T_i = gap_0 + ... + gap_i.
 Parity status: every function below is pinned by tests/test_oracle_*.py against
 closed forms, brute force in rational arithmetic, library routines and
 invariants; none is "parity unpinned".
@@ -283,3 +292,30 @@ def loqt_init_compensate(W, P, s, iters, B0=None):
         B = (Pinv @ (Wd - Q)) / s
         history.append(float(np.linalg.norm(Q + s * (Pd @ B) - Wd)))
     return codes, absmax, B, history
+
+
+# ----------------------------------------------------------------------------
+# the step between merges (Alg. 1 line 9) and the merge schedule (sec. 2.5)
+# ----------------------------------------------------------------------------
+def adam_step(B, g, m, v, lr, beta1, beta2, eps, t):
+    """One Adam update of B (float64 arrays; t = 1, 2, ... is the step count).  Returns (B, m, v)."""
+    m = beta1 * m + (1.0 - beta1) * g
+    v = beta2 * v + (1.0 - beta2) * g * g
+    m_hat = m / (1.0 - beta1 ** t)
+    v_hat = v / (1.0 - beta2 ** t)
+    return B - lr * m_hat / (np.sqrt(v_hat) + eps), m, v
+
+
+def merge_schedule(tau, psi, cap, n):
+    """The first n steps T_i at which W is updated: gaps min(cap, floor(tau + psi**i)), accumulated."""
+    steps, t = [], 0
+    for i in range(n):
+        t += min(int(cap), int(np.floor(tau + psi ** i)))
+        steps.append(t)
+    return steps
+
+
+def loqt_merge_dense_f32(Wq, Pq, B, s):
+    """Alg. 1 line 5 as printed: W <- W_Q + s P_Q B, kept in full precision (fp32 of the fp64 sum);
+    the input of Alg. 2's Initialize."""
+    return loqt_merge_f64(Wq, Pq, B, s).astype(np.float32)
