@@ -233,6 +233,46 @@ loqt_status loqt_init_compensate(const float *W, int64_t ld_w, const float *P, i
                                  void *hip_stream);
 
 /*
+ * loqt_merge_dense -- Alg. 1 line 5 as printed: W <- W_Q + s P_Q B in full precision, the input of
+ * Alg. 2's Initialize (a new P from the gradient, then loqt_init_compensate on this W).
+ *   W_out[out x in] (fp32, pitch ld_out, ld_out % 4 == 0, 16-byte aligned) =
+ *       fl32(M * q[code]) + s * (fp32-accumulated bf16 product deq(Pq) B), one fused multiply-add;
+ * nf4_quantize(W_out) reproduces loqt_merge_requant bit for bit.  Workspace: LOQT_OP_MERGE.
+ */
+loqt_status loqt_merge_dense(const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq, const loqt_bf16 *B,
+                             int64_t ld_B, float s, float *W_out, int64_t ld_out,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * loqt_adam_step -- the update between merges (Alg. 1 line 9: B_{t+1} = B_t - rho(G^B_t), rho = Adam;
+ * the paper names the optimiser only, so this is the published algorithm with bias correction and no
+ * weight decay):
+ *     m = beta1 m + (1 - beta1) g ;  v = beta2 v + (1 - beta2) g^2
+ *     B = B - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *   B    : bf16 rows x cols (pitch ld_B), updated in place (fp32 arithmetic, one rounding to bf16)
+ *   grad : LOQT_F32 or LOQT_BF16, pitch ld_grad >= cols (what loqt_linear_bwd wrote into dB)
+ *   m, v : fp32 moments, pitch ld_mv >= cols, updated in place (zero them before step 1, and again
+ *          whenever B is re-initialised after a merge)
+ *   step : 1, 2, ...;  lr >= 0, 0 <= beta < 1, eps >= 0
+ * Works for either factor (B of the left form, Bp of the right form).
+ */
+loqt_status loqt_adam_step(loqt_bf16 *B, int64_t ld_B, int64_t rows, int64_t cols,
+                           const void *grad, int grad_dtype, int64_t ld_grad,
+                           float *m, float *v, int64_t ld_mv,
+                           float lr, float beta1, float beta2, float eps, int64_t step,
+                           void *hip_stream);
+
+/*
+ * loqt_merge_schedule -- the steps at which W is updated (sec. 2.5 last paragraph: intervals that
+ * start at tau and grow by a factor psi; hyper-parameter appendix: tau = 100, psi = 1.2; the
+ * ablation of update intervals caps them at 2500).  HOST function, no GPU work:
+ *     gap_i = min(cap, floor(tau + psi^i)),   steps_out[i] = gap_0 + ... + gap_i,   i = 0..n-1
+ * (the text also prints T_i = tau + psi^i for the steps themselves; growing intervals are the
+ * reading that matches "starting at 100 ... up to 2500").  steps_out: HOST array of n entries.
+ */
+loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int64_t *steps_out);
+
+/*
  * Implementation choice (process-wide; not thread-safe; default LOQT_PATH_AUTO).
  *   LOQT_PATH_FUSED  : NF4 codes are expanded inside the GEMMs' operand staging (global memory
  *                      -> registers -> LDS), no extra pass over the weights.

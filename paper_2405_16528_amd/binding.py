@@ -70,6 +70,12 @@ lib.loqt_linear_bwd_right.restype = _i
 lib.loqt_linear_bwd_right.argtypes = lib.loqt_linear_bwd.argtypes
 lib.loqt_merge_requant_right.restype = _i
 lib.loqt_merge_requant_right.argtypes = lib.loqt_merge_requant.argtypes
+lib.loqt_merge_dense.restype = _i
+lib.loqt_merge_dense.argtypes = [_P(NF4MatC), _P(NF4MatC), _vp, _i64, _f, _vp, _i64, _vp, _sz, _vp]
+lib.loqt_adam_step.restype = _i
+lib.loqt_adam_step.argtypes = [_vp, _i64, _i64, _i64, _vp, _i, _i64, _vp, _vp, _i64, _f, _f, _f, _f, _i64, _vp]
+lib.loqt_merge_schedule.restype = _i
+lib.loqt_merge_schedule.argtypes = [C.c_double, C.c_double, _i64, _i, _P(_i64)]
 lib.loqt_init_compensate.restype = _i
 lib.loqt_init_compensate.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _f, _i, _i, _vp, _vp, _i64, _vp, _i64,
                                      _vp, _sz, _vp]
@@ -231,6 +237,32 @@ def loqt_merge_requant_right(Wq: NF4Tensor, Qq: NF4Tensor, Bp, s: float, out: Op
                                         C.byref(Qq.c()), Bp.data_ptr(), _pitch(Bp), s, *_ws_args(ws), _stream()),
            "loqt_merge_requant_right")
     return out
+
+
+def loqt_merge_dense(Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, W_out: torch.Tensor,
+                     ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """W_out: float32 (out, >= in): the unquantised merged weight deq(Wq) + s deq(Pq) B."""
+    if ws is None:
+        ws = workspace(OP_MERGE, 0, Wq.rows, Wq.cols, Pq.cols, Wq.codes.device)
+    _check(lib.loqt_merge_dense(C.byref(Wq.c()), C.byref(Pq.c()), B.data_ptr(), _pitch(B), s, W_out.data_ptr(),
+                                _pitch(W_out), *_ws_args(ws), _stream()), "loqt_merge_dense")
+    return W_out
+
+
+def loqt_adam_step(B: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torch.Tensor, lr: float, step: int,
+                   beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+    """B bfloat16 (rows, cols) updated in place; grad float32 or bfloat16; m, v float32."""
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[grad.dtype]
+    _check(lib.loqt_adam_step(B.data_ptr(), _pitch(B), B.shape[0], B.shape[1], grad.data_ptr(), dt, _pitch(grad),
+                              m.data_ptr(), v.data_ptr(), _pitch(m), lr, beta1, beta2, eps, step, _stream()),
+           "loqt_adam_step")
+
+
+def loqt_merge_schedule(n: int, tau: float = 100.0, psi: float = 1.2, cap: int = 2500):
+    """The first n steps at which W is updated (host computation)."""
+    arr = (_i64 * n)()
+    _check(lib.loqt_merge_schedule(tau, psi, cap, n, arr), "loqt_merge_schedule")
+    return list(arr)
 
 
 def loqt_init_compensate(W: torch.Tensor, P: torch.Tensor, s: float, iters: int, B: torch.Tensor,

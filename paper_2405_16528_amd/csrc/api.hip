@@ -1,4 +1,5 @@
 // C ABI of libloqt: argument checking, workspace layout, launch sequences, timing.
+#include <math.h>
 #include <string.h>
 
 #include <algorithm>
@@ -21,7 +22,7 @@ struct TimingState {
 } g_timing;
 const char* kSlotNames[SLOT_COUNT] = {"nf4_quantize", "nf4_dequantize", "gemm_u",   "gemm_y",      "gemm_z",
                                       "gemm_dx",      "gemm_db",        "reduce_db", "merge_requant", "prepass", "fold_weight",
-                                      "init_requant", "init_solve_b"};
+                                      "init_requant", "init_solve_b", "merge_dense", "adam_step"};
 }  // namespace
 
 TimedLaunch::TimedLaunch(int slot_, hipStream_t s) : stream(s), slot(slot_), idx(-1) {
@@ -855,6 +856,70 @@ loqt_status loqt_merge_requant_right(const loqt_nf4_mat* Wq, uint8_t* codes_out,
     p.w_ld = Wq->ld;
     p.w_cols = (int)in;
     LOQT_HIP(launch_gemm_nt(SLOT_MERGE, EPI_MERGE, false, false, p, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_merge_dense(const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B,
+                             float s, float* W_out, int64_t ld_out, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!W_out) return LOQT_INVALID_ARG;
+    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
+    const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
+    if (ld_out < 0) return LOQT_INVALID_ARG;
+    if (ld_out % 4 != 0 || ld_out < in) return LOQT_BAD_SHAPE;
+    if (!aligned(W_out, 16)) return LOQT_MISALIGNED;
+    const MergeWs L(out, in, r);
+    if (!ws) return LOQT_INVALID_ARG;
+    if (!aligned(ws, 256)) return LOQT_MISALIGNED;
+    if (ws_bytes < L.total) return LOQT_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint16_t* Pb = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(ws) + L.Pb);
+    const int64_t ldr = (int64_t)round_up(r, 8);
+    LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ldr, st, SLOT_PREPASS));
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(Pb, ldr, (int)out, (int)r);
+    p.B[0] = bf16_operand(B, ld_B, (int)in, (int)r);  // r x in: K x rows
+    p.M = (int)out;
+    p.N = (int)in;
+    p.alpha = s;
+    p.C = W_out;
+    p.ldc = ld_out;
+    p.splits = 1;
+    p.w_codes = Wq->codes;
+    p.w_absmax = Wq->absmax;
+    p.w_ld = Wq->ld;
+    p.w_cols = (int)in;
+    LOQT_HIP(launch_gemm_nt(SLOT_MERGE_DENSE, EPI_FOLD_F32, false, true, p, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_adam_step(loqt_bf16* B, int64_t ld_B, int64_t rows, int64_t cols, const void* grad, int grad_dtype,
+                           int64_t ld_grad, float* m, float* v, int64_t ld_mv, float lr, float beta1, float beta2,
+                           float eps, int64_t step, void* hip_stream) {
+    if (!grad || !m || !v) return LOQT_INVALID_ARG;
+    if (grad_dtype != LOQT_F32 && grad_dtype != LOQT_BF16) return LOQT_INVALID_ARG;
+    if (step < 1 || !(lr >= 0.f) || !(eps >= 0.f) || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+        return LOQT_INVALID_ARG;
+    LOQT_TRY(check_bf16(B, rows, cols, ld_B));
+    if (ld_grad < cols || ld_mv < cols) return LOQT_BAD_SHAPE;
+    if (!aligned(grad, grad_dtype == LOQT_BF16 ? 2 : 4) || !aligned(m, 4) || !aligned(v, 4)) return LOQT_MISALIGNED;
+    // bias corrections in double on the host
+    const double bc1 = 1.0 / (1.0 - pow((double)beta1, (double)step));
+    const double bc2 = 1.0 / (1.0 - pow((double)beta2, (double)step));
+    LOQT_HIP(launch_adam(B, ld_B, grad, grad_dtype, ld_grad, m, v, ld_mv, rows, cols, lr, beta1, beta2, eps,
+                         (float)bc1, (float)bc2, (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int64_t* steps_out) {
+    if (!steps_out || n < 0) return LOQT_INVALID_ARG;
+    if (!(tau >= 1.0) || !(psi >= 1.0) || cap < 1) return LOQT_INVALID_ARG;
+    int64_t t = 0;
+    for (int i = 0; i < n; ++i) {
+        const double gap = floor(tau + pow(psi, (double)i));  // +inf once psi^i overflows: capped below
+        t += gap >= (double)cap ? cap : (int64_t)gap;
+        steps_out[i] = t;
+    }
     return LOQT_OK;
 }
 

@@ -344,28 +344,57 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 }
             }
         }
-    } else if (EPI == EPI_F32_SPLITK) {
-        float* C = reinterpret_cast<float*>(p.C) + (int64_t)blockIdx.y * p.M * p.ldc;
+    } else if (EPI == EPI_F32_SPLITK || EPI == EPI_FOLD_F32) {
+        // fp32 results, 16 bytes per lane (row m, 4 consecutive n).  EPI_F32_SPLITK: slice blockIdx.y of the
+        // contraction.  EPI_FOLD_F32 (M = out, N = in): the dense merged weight of Alg. 1 line 5,
+        // fma(alpha, acc, fl32(absmax * q[code])), the same expression the merge epilogue quantises.
+        float* C = reinterpret_cast<float*>(p.C);
+        if (EPI == EPI_F32_SPLITK) C += (int64_t)blockIdx.y * p.M * p.ldc;
+        float* lut = reinterpret_cast<float*>(smem);
+        if (EPI == EPI_FOLD_F32) {
+            if (tid < 16) lut[tid] = kNf4Levels[tid];
+            __syncthreads();
+        }
+        const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
 #pragma unroll
         for (int ti = 0; ti < TM; ++ti) {
             const int m = m0 + wm * Cfg::WTM + ti * 32 + frow;
 #pragma unroll
-            for (int tj = 0; tj < TN; ++tj)
+            for (int tj = 0; tj < TN; ++tj) {
+                uint32_t cw4[4] = {0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};
+                float am = 0.f;
+                if (EPI == EPI_FOLD_F32) {
+                    const int nt = n0 + wn * Cfg::WTN + tj * 32;
+                    if (m < p.M && nt < p.w_ld) {
+                        const uint4 c = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nt >> 1));
+                        cw4[0] = c.x, cw4[1] = c.y, cw4[2] = c.z, cw4[3] = c.w;
+                        am = p.w_absmax[m * lda + (nt >> 6)];
+                    }
+                }
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int n = n0 + wn * Cfg::WTN + tj * 32 + 8 * g + 4 * h;
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (EPI == EPI_FOLD_F32) {
+                            const uint32_t cw = (cw4[g] >> (16 * h)) & 0xffffu;
+                            v[j] = __builtin_fmaf(p.alpha, acc[ti][tj][4 * g + j], am * lut[nib4(cw, j)]);
+                        } else {
+                            v[j] = p.alpha * acc[ti][tj][4 * g + j];
+                        }
+                    }
                     if (m < p.M) {
                         float* dst = C + (int64_t)m * p.ldc + n;
                         if (n + 4 <= p.N) {
-                            *reinterpret_cast<float4*>(dst) =
-                                make_float4(p.alpha * acc[ti][tj][4 * g + 0], p.alpha * acc[ti][tj][4 * g + 1],
-                                            p.alpha * acc[ti][tj][4 * g + 2], p.alpha * acc[ti][tj][4 * g + 3]);
+                            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
                         } else {
                             for (int j = 0; j < 4; ++j)
-                                if (n + j < p.N) dst[j] = p.alpha * acc[ti][tj][4 * g + j];
+                                if (n + j < p.N) dst[j] = v[j];
                         }
                     }
                 }
+            }
         }
     } else {
         // merge (M = out, N = in): W_new = fl32(absmax * q[code]) + alpha * acc, requantised per
@@ -505,7 +534,7 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     // or a heavy epilogue (merge, fp32 slices; measured on real data, the fold is better off with the
     // large tile) two or three resident 128x128 work-groups per
     // compute unit win: the epilogue and prologue of one overlap with the main loop of another.
-    if constexpr (EPI == EPI_COMP) {
+    if constexpr (EPI == EPI_COMP || EPI == EPI_FOLD_F32) {
         return launch_nt<128, 128, EPI, ARC, BRC>(p, st);  // heavy epilogue: small tiles only
     } else {
     int choice = g_nt_tile_override;
@@ -565,6 +594,7 @@ hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmPar
             case EPI_MERGE: return launch_nt_sized<EPI_MERGE, false, true>(p, st);
             case EPI_FOLD: return launch_nt_sized<EPI_FOLD, false, true>(p, st);
             case EPI_COMP: return launch_nt_sized<EPI_COMP, false, true>(p, st);
+            case EPI_FOLD_F32: return launch_nt_sized<EPI_FOLD_F32, false, true>(p, st);
             default: break;
         }
     } else if (a_rc && b_rc) {

@@ -129,6 +129,8 @@ enum KernelSlot {
     SLOT_FOLD,        // W_eff = deq(W) + s deq(P) B in bf16 (folded path)
     SLOT_INIT_Q,      // compensation loop: Q_c = q(W - s P B) and the residual W - deq(Q_c)
     SLOT_INIT_B,      // compensation loop: B = P^T (W - deq(Q_c)) / s (fp32 slices)
+    SLOT_MERGE_DENSE, // W = deq(W_q) + s deq(P_q) B in fp32 (Alg. 1 line 5 without requantisation)
+    SLOT_ADAM,        // Adam step on B
     SLOT_COUNT
 };
 
@@ -148,6 +150,10 @@ hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t l
 hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t rows, int64_t cols,
                              int64_t ld_q, void* out, int out_dtype, int64_t ld_out, hipStream_t st,
                              int slot = SLOT_DEQUANTIZE);
+// Adam on a bf16 matrix with fp32 moments (bias corrections bc1 = 1/(1-beta1^t), bc2 = 1/(1-beta2^t) from the host)
+hipError_t launch_adam(uint16_t* B, int64_t ld_B, const void* g, int g_dtype, int64_t ld_g, float* m, float* v,
+                       int64_t ld_mv, int64_t rows, int64_t cols, float lr, float beta1, float beta2, float eps,
+                       float bc1, float bc2, hipStream_t st);
 // fp32 rows x cols (pitch ld_in, 16-byte aligned rows) -> bf16 (pitch ld_out, multiple of 8), round to nearest even
 hipError_t launch_f32_to_bf16(const float* in, int64_t rows, int64_t cols, int64_t ld_in, uint16_t* out,
                               int64_t ld_out, hipStream_t st);
@@ -169,7 +175,7 @@ struct Operand {
     int K;                // extent along the contraction
 };
 
-enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3, EPI_COMP = 4 };
+enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3, EPI_COMP = 4, EPI_FOLD_F32 = 5 };
 
 struct GemmParams {
     Operand A[2], B[2];  // up to two K segments; segment 1 unused when A[1].K == 0

@@ -26,7 +26,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"nf4_quantize", "nf4_dequantize", "loqt_linear_fwd", "loqt_linear_bwd", "loqt_merge_requant",
             "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path",
             "loqt_init_compensate", "loqt_linear_fwd_right", "loqt_linear_bwd_right",
-            "loqt_merge_requant_right"} <= names
+            "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -111,6 +111,17 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.loqt_merge_requant_right(C.byref(W), P + 64, P, C.byref(Qm), P, 128, 1.0, P, ws, None) == 1
     assert lib.loqt_merge_requant_right(C.byref(W), P, P, C.byref(Qm), P, 128, 1.0, None, ws, None) == 1
 
+    assert lib.loqt_merge_dense(C.byref(W), C.byref(Pm), P, 512, 1.0, None, 512, P, ws, None) == 1
+    assert lib.loqt_merge_dense(C.byref(W), C.byref(Pm), P, 512, 1.0, P, 510, P, ws, None) == 2
+    assert lib.loqt_merge_dense(C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 16, None) == 4
+    assert lib.loqt_adam_step(P, 512, 128, 512, P, 0, 512, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 0, None) == 1   # step 0
+    assert lib.loqt_adam_step(P, 512, 128, 512, P, 0, 512, P, P, 512, 1e-3, 1.0, 0.999, 1e-8, 1, None) == 1   # beta1 = 1
+    assert lib.loqt_adam_step(P, 512, 128, 512, P, 7, 512, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 1   # dtype
+    assert lib.loqt_adam_step(P, 512, 128, 512, P, 0, 100, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 2   # ld_grad
+    assert lib.loqt_adam_step(P, 512, 128, 512, None, 0, 512, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 1
+    assert lib.loqt_merge_schedule(100.0, 1.2, 2500, 4, None) == 1
+    assert lib.loqt_merge_schedule(100.0, 0.5, 2500, 0, (C.c_int64 * 1)()) == 1                            # psi < 1
+
     def init(W=P, ld_w=512, Pp=P, ld_p=128, out=512, inp=512, r=128, s=1.0, iters=3, warm=0, codes=P, am=P, ld_q=512,
              B=P, ld_B=512, w=P, wsb=ws):
         return lib.loqt_init_compensate(W, ld_w, Pp, ld_p, out, inp, r, s, iters, warm, codes, am, ld_q, B, ld_B, w,
@@ -121,3 +132,13 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert init(ld_B=100) == 2
     assert init(W=P + 4) == 3 and init(w=P + 64) == 3
     assert init(w=None) == 1 and init(wsb=1024) == 4
+
+
+def test_merge_schedule_matches_the_oracle(lib):
+    """loqt_merge_schedule is host code: it runs without a GPU and must reproduce the oracle's steps."""
+    from oracle import loqt_oracle as O
+    from paper_2405_16528_amd import binding as L
+    assert L.loqt_merge_schedule(60) == O.merge_schedule(100, 1.2, 2500, 60)
+    assert L.loqt_merge_schedule(5, tau=200.0, psi=1.0) == [201, 402, 603, 804, 1005]
+    assert L.loqt_merge_schedule(200, tau=50.0, psi=1.5, cap=300) == O.merge_schedule(50, 1.5, 300, 200)
+    assert L.loqt_merge_schedule(0) == []
