@@ -26,7 +26,11 @@
  *     and the call returns without synchronising;
  *   - arguments are checked on the host; on error a status is returned and NOTHING is
  *     launched.  No exceptions, no hidden state, results are bit-deterministic;
- *   - inputs must be finite.
+ *   - inputs must be finite;
+ *   - the calls can be recorded into a HIP graph (stream capture): they allocate nothing, record
+ *     no memset nodes and synchronise with nothing.  The first launch of each kernel configuration
+ *     in a process sets its LDS size with hipFuncSetAttribute, so run every call once eagerly with
+ *     the shapes in question before capturing it.
  *
  * NF4 storage (sec. 5.1: blocks of 64 weights, one scale M_beta = max |w| per block)
  *   codes  : rows x ld nibbles, two per byte.  Row i starts at byte i*ld/2; element j of
