@@ -22,6 +22,8 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
           m > n the same reasoning holds for Q^T"): the projection sits on the input side,
       W_eff = deq(W_q) + s * Bp @ deq(Q_q)^T   Q in x r fixed (NF4), Bp out x r trainable;
       y = x @ W_eff^T ; dx = dy @ W_eff ; dBp = s * dy^T @ (x @ deq(Q_q))
+  nq     (the paper's LoQT-nq, "no quantization": the same layer with W and P kept in 16 bits):
+      W_eff = W + s * P @ B with W, P bf16;  merge: W <- bf16(W + s P B)
   init   (Alg. 2 lines 5-11, sec. 2.5 "Compensating for Quantization Errors"): with P
           fixed, alternate  Q_c = q_NF4(W_hat) ;  B = P^+ (W - Q_c) / s ;
           W_hat = W - s P B,  so that Q_c + s P B approximates W.
@@ -258,6 +260,32 @@ def loqt_linear_bwd_right(dy, x, Wq, Qq, Bp, s):
 def loqt_merge_requant_right(Wq, Qq, Bp, s):
     """W_q <- q_NF4( fp32( deq(W_q) + s Bp deq(Q_q)^T ) )  (Alg. 1 line 5 for the right-side form)."""
     return nf4_quantize(loqt_right_weff_f64(Wq, Qq, Bp, s).astype(np.float32))
+
+
+# ----------------------------------------------------------------------------
+# LoQT-nq: the layer without quantisation (W and P in bf16)
+# ----------------------------------------------------------------------------
+def loqt_linear_fwd_nq(x, W, P, B, s):
+    """y = x W^T + s (x B^T) P^T  (float64); W (out, in), P (out, r), B (r, in), x (T, in): bf16 bits."""
+    xd = bf16_to_f64(x)
+    return xd @ bf16_to_f64(W).T + s * ((xd @ bf16_to_f64(B).T) @ bf16_to_f64(P).T)
+
+
+def loqt_linear_bwd_nq(dy, x, W, P, B, s):
+    """dx = dy W + s (dy P) B ;  dB = s P^T dy^T x  (float64)."""
+    dyd, xd = bf16_to_f64(dy), bf16_to_f64(x)
+    Z = dyd @ bf16_to_f64(P)
+    return dyd @ bf16_to_f64(W) + s * (Z @ bf16_to_f64(B)), s * (Z.T @ xd)
+
+
+def loqt_merge_nq_f64(W, P, B, s):
+    """W + s P B in float64 (Alg. 1 line 5 without quantisation)."""
+    return bf16_to_f64(W) + s * (bf16_to_f64(P) @ bf16_to_f64(B))
+
+
+def loqt_merge_nq(W, P, B, s):
+    """W <- bf16(fp32(W + s P B)), round to nearest even; returns bf16 bits."""
+    return f32_to_bf16_rne(loqt_merge_nq_f64(W, P, B, s).astype(np.float32))
 
 
 # ----------------------------------------------------------------------------
