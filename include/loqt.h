@@ -75,7 +75,8 @@ typedef struct loqt_nf4_mat {
 
 enum { LOQT_F32 = 0, LOQT_BF16 = 1 };                 /* output dtypes */
 enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2, LOQT_OP_INIT = 3,
-       LOQT_OP_FWD_RIGHT = 4, LOQT_OP_BWD_RIGHT = 5, LOQT_OP_MERGE_RIGHT = 6 };
+       LOQT_OP_FWD_RIGHT = 4, LOQT_OP_BWD_RIGHT = 5, LOQT_OP_MERGE_RIGHT = 6,
+       LOQT_OP_FWD_NQ = 7, LOQT_OP_BWD_NQ = 8 };
 
 /* Human-readable name of a status code (static string). */
 const char *loqt_status_string(loqt_status st);
@@ -115,6 +116,7 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
  *   FWD_RIGHT, BWD_RIGHT, MERGE_RIGHT: the right-side variant below, with r = columns of Q_q:
  *          bf16 deq(Q_q); forward and backward + the folded weight (out x in bf16); backward +
  *          V = s x deq(Q_q) (T x r bf16) and fp32 slices of dBp
+ *   FWD_NQ, BWD_NQ: the unquantised variant below: U resp. Z (T x r bf16) and the fp32 slices of dB
  */
 size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r);
 
@@ -235,6 +237,31 @@ loqt_status loqt_init_compensate(const float *W, int64_t ld_w, const float *P, i
                                  int warm_start, uint8_t *codes_out, float *absmax_out, int64_t ld_q,
                                  loqt_bf16 *B, int64_t ld_B, void *ws, size_t ws_bytes,
                                  void *hip_stream);
+
+/*
+ * LoQT-nq -- the method without quantisation (the paper's "LoQT-nq": W and P stay in 16 bits).  Same
+ * layer, same gradients, with bf16 matrices W (out x in, pitch ld_W) and P (out x r, pitch ld_P) in
+ * place of the NF4 ones:
+ *   loqt_linear_fwd_nq   y  = x W^T + s (x B^T) P^T
+ *   loqt_linear_bwd_nq   dx = dy W + s (dy P) B  (dx may be NULL),  dB = s P^T dy^T x  (as loqt_linear_bwd)
+ *   loqt_merge_nq        W <- bf16( fp32(W) + s * P B ), in place, round to nearest even (Alg. 1 line 5)
+ * Nothing is dequantised, so the rank-r term is carried as a second K segment of the products
+ * ([x | U] [W | P]^T and [dy | Z] [W ; B]) and no pass over the weights precedes them.
+ */
+loqt_status loqt_linear_fwd_nq(const loqt_bf16 *x, int64_t ld_x, int64_t T,
+                               const loqt_bf16 *W, int64_t ld_W, const loqt_bf16 *P, int64_t ld_P,
+                               const loqt_bf16 *B, int64_t ld_B, int64_t out, int64_t in, int64_t r,
+                               float s, loqt_bf16 *y, int64_t ld_y,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+loqt_status loqt_linear_bwd_nq(const loqt_bf16 *dy, int64_t ld_dy, const loqt_bf16 *x, int64_t ld_x,
+                               int64_t T, const loqt_bf16 *W, int64_t ld_W, const loqt_bf16 *P,
+                               int64_t ld_P, const loqt_bf16 *B, int64_t ld_B, int64_t out, int64_t in,
+                               int64_t r, float s, loqt_bf16 *dx, int64_t ld_dx,
+                               void *dB, int dB_dtype, int64_t ld_dB, int accumulate,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+loqt_status loqt_merge_nq(loqt_bf16 *W, int64_t ld_W, const loqt_bf16 *P, int64_t ld_P,
+                          const loqt_bf16 *B, int64_t ld_B, int64_t out, int64_t in, int64_t r,
+                          float s, void *hip_stream);
 
 /*
  * loqt_merge_dense -- Alg. 1 line 5 as printed: W <- W_Q + s P_Q B in full precision, the input of

@@ -23,6 +23,7 @@ lib = C.CDLL(_LIB_PATH)
 
 F32, BF16 = 0, 1
 OP_FWD, OP_BWD, OP_MERGE, OP_INIT, OP_FWD_RIGHT, OP_BWD_RIGHT, OP_MERGE_RIGHT = 0, 1, 2, 3, 4, 5, 6
+OP_FWD_NQ, OP_BWD_NQ = 7, 8
 PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
                 4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
@@ -70,6 +71,14 @@ lib.loqt_linear_bwd_right.restype = _i
 lib.loqt_linear_bwd_right.argtypes = lib.loqt_linear_bwd.argtypes
 lib.loqt_merge_requant_right.restype = _i
 lib.loqt_merge_requant_right.argtypes = lib.loqt_merge_requant.argtypes
+lib.loqt_linear_fwd_nq.restype = _i
+lib.loqt_linear_fwd_nq.argtypes = [_vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _f, _vp, _i64,
+                                   _vp, _sz, _vp]
+lib.loqt_linear_bwd_nq.restype = _i
+lib.loqt_linear_bwd_nq.argtypes = [_vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _f,
+                                   _vp, _i64, _vp, _i, _i64, _i, _vp, _sz, _vp]
+lib.loqt_merge_nq.restype = _i
+lib.loqt_merge_nq.argtypes = [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _f, _vp]
 lib.loqt_merge_dense.restype = _i
 lib.loqt_merge_dense.argtypes = [_P(NF4MatC), _P(NF4MatC), _vp, _i64, _f, _vp, _i64, _vp, _sz, _vp]
 lib.loqt_adam_step.restype = _i
@@ -237,6 +246,33 @@ def loqt_merge_requant_right(Wq: NF4Tensor, Qq: NF4Tensor, Bp, s: float, out: Op
                                         C.byref(Qq.c()), Bp.data_ptr(), _pitch(Bp), s, *_ws_args(ws), _stream()),
            "loqt_merge_requant_right")
     return out
+
+
+def loqt_linear_fwd_nq(x, W, P, B, s: float, y, ws) -> torch.Tensor:
+    """LoQT-nq: W (out, in), P (out, r), B (r, in) bfloat16."""
+    out, inp, r = W.shape[0], W.shape[1], P.shape[1]
+    _check(lib.loqt_linear_fwd_nq(x.data_ptr(), _pitch(x), x.shape[0], W.data_ptr(), _pitch(W), P.data_ptr(), _pitch(P),
+                                  B.data_ptr(), _pitch(B), out, inp, r, s, y.data_ptr(), _pitch(y), *_ws_args(ws),
+                                  _stream()), "loqt_linear_fwd_nq")
+    return y
+
+
+def loqt_linear_bwd_nq(dy, x, W, P, B, s: float, dx, dB, accumulate: bool, ws):
+    out, inp, r = W.shape[0], W.shape[1], P.shape[1]
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[dB.dtype]
+    _check(lib.loqt_linear_bwd_nq(dy.data_ptr(), _pitch(dy), x.data_ptr(), _pitch(x), x.shape[0], W.data_ptr(),
+                                  _pitch(W), P.data_ptr(), _pitch(P), B.data_ptr(), _pitch(B), out, inp, r, s,
+                                  _ptr(dx), _pitch(dx) if dx is not None else 0, dB.data_ptr(), dt, _pitch(dB),
+                                  1 if accumulate else 0, *_ws_args(ws), _stream()), "loqt_linear_bwd_nq")
+    return dx, dB
+
+
+def loqt_merge_nq(W, P, B, s: float) -> torch.Tensor:
+    """W <- bf16(W + s P B) in place."""
+    out, inp, r = W.shape[0], W.shape[1], P.shape[1]
+    _check(lib.loqt_merge_nq(W.data_ptr(), _pitch(W), P.data_ptr(), _pitch(P), B.data_ptr(), _pitch(B), out, inp, r, s,
+                             _stream()), "loqt_merge_nq")
+    return W
 
 
 def loqt_merge_dense(Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, W_out: torch.Tensor,

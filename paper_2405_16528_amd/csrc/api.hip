@@ -402,6 +402,12 @@ size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t 
             if (T <= 0) return 0;
             return RightWs(op, T, out, in, r).total;
         case LOQT_OP_MERGE_RIGHT: return RightWs(op, 0, out, in, r).total;
+        case LOQT_OP_FWD_NQ: return T <= 0 ? 0 : bf16_bytes(T, r);
+        case LOQT_OP_BWD_NQ: {
+            if (T <= 0) return 0;
+            const BwdWs L(T, out, in, r);
+            return bf16_bytes(T, r) + (L.total - L.partials);
+        }
         default: return 0;
     }
 }
@@ -920,6 +926,129 @@ loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int6
         t += gap >= (double)cap ? cap : (int64_t)gap;
         steps_out[i] = t;
     }
+    return LOQT_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// LoQT-nq: W and P in bf16, no quantisation anywhere
+// ---------------------------------------------------------------------------------------
+namespace {
+loqt_status check_layer_nq(const loqt_bf16* W, int64_t ld_W, const loqt_bf16* P, int64_t ld_P, const loqt_bf16* B,
+                           int64_t ld_B, int64_t out, int64_t in, int64_t r) {
+    LOQT_TRY(check_bf16(W, out, in, ld_W));
+    LOQT_TRY(check_bf16(P, out, r, ld_P));
+    LOQT_TRY(check_bf16(B, r, in, ld_B));
+    return LOQT_OK;
+}
+}  // namespace
+
+loqt_status loqt_linear_fwd_nq(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_bf16* W, int64_t ld_W,
+                               const loqt_bf16* P, int64_t ld_P, const loqt_bf16* B, int64_t ld_B, int64_t out,
+                               int64_t in, int64_t r, float s, loqt_bf16* y, int64_t ld_y, void* ws,
+                               size_t ws_bytes, void* hip_stream) {
+    LOQT_TRY(check_layer_nq(W, ld_W, P, ld_P, B, ld_B, out, in, r));
+    LOQT_TRY(check_bf16(x, T, in, ld_x));
+    LOQT_TRY(check_bf16(y, T, out, ld_y));
+    LOQT_TRY(check_ws(ws, ws_bytes, bf16_bytes(T, r)));
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint16_t* U = reinterpret_cast<uint16_t*>(ws);
+    const int64_t ld_u = (int64_t)round_up(r, 8);
+    GemmParams p;
+    memset(&p, 0, sizeof(p));  // U = s x B^T
+    p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+    p.B[0] = bf16_operand(B, ld_B, (int)r, (int)in);
+    p.M = (int)T;
+    p.N = (int)r;
+    p.alpha = s;
+    p.C = U;
+    p.ldc = ld_u;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_U, EPI_BF16, false, false, p, st));
+    memset(&p, 0, sizeof(p));  // y = [x | U] [W | P]^T
+    p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+    p.B[0] = bf16_operand(W, ld_W, (int)out, (int)in);
+    p.A[1] = bf16_operand(U, ld_u, (int)T, (int)r);
+    p.B[1] = bf16_operand(P, ld_P, (int)out, (int)r);
+    p.M = (int)T;
+    p.N = (int)out;
+    p.alpha = 1.0f;
+    p.C = y;
+    p.ldc = ld_y;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, false, false, p, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_linear_bwd_nq(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
+                               const loqt_bf16* W, int64_t ld_W, const loqt_bf16* P, int64_t ld_P,
+                               const loqt_bf16* B, int64_t ld_B, int64_t out, int64_t in, int64_t r, float s,
+                               loqt_bf16* dx, int64_t ld_dx, void* dB, int dB_dtype, int64_t ld_dB, int accumulate,
+                               void* ws, size_t ws_bytes, void* hip_stream) {
+    LOQT_TRY(check_layer_nq(W, ld_W, P, ld_P, B, ld_B, out, in, r));
+    LOQT_TRY(check_bf16(dy, T, out, ld_dy));
+    LOQT_TRY(check_bf16(x, T, in, ld_x));
+    if (dx) LOQT_TRY(check_bf16(dx, T, in, ld_dx));
+    if (!dB) return LOQT_INVALID_ARG;
+    if (dB_dtype != LOQT_F32 && dB_dtype != LOQT_BF16) return LOQT_INVALID_ARG;
+    if (ld_dB < in) return LOQT_BAD_SHAPE;
+    if (!aligned(dB, dB_dtype == LOQT_BF16 ? 2 : 4)) return LOQT_MISALIGNED;
+    const BwdWs L(T, out, in, r);  // only its split choice and slice pitch are used here
+    const size_t z_bytes = bf16_bytes(T, r);
+    LOQT_TRY(check_ws(ws, ws_bytes, z_bytes + (L.total - L.partials)));
+    hipStream_t st = (hipStream_t)hip_stream;
+    uint16_t* Z = reinterpret_cast<uint16_t*>(ws);
+    float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + z_bytes);
+    const int64_t ld_z = (int64_t)round_up(r, 8);
+    GemmParams p;
+    memset(&p, 0, sizeof(p));  // Z = s dy P: P is out x r, i.e. K x rows
+    p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+    p.B[0] = bf16_operand(P, ld_P, (int)r, (int)out);
+    p.M = (int)T;
+    p.N = (int)r;
+    p.alpha = s;
+    p.C = Z;
+    p.ldc = ld_z;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, false, true, p, st));
+    if (dx) {  // dx = [dy | Z] [W ; B]: W is out x in and B is r x in, both K x rows
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
+        p.B[0] = bf16_operand(W, ld_W, (int)in, (int)out);
+        p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
+        p.B[1] = bf16_operand(B, ld_B, (int)in, (int)r);
+        p.M = (int)T;
+        p.N = (int)in;
+        p.alpha = 1.0f;
+        p.C = dx;
+        p.ldc = ld_dx;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, false, true, p, st));
+    }
+    memset(&p, 0, sizeof(p));  // dB = Z^T x over slices of T
+    p.A[0] = bf16_operand(Z, ld_z, (int)r, (int)T);
+    p.B[0] = bf16_operand(x, ld_x, (int)in, (int)T);
+    p.M = (int)r;
+    p.N = (int)in;
+    p.alpha = 1.0f;
+    p.C = part;
+    p.ldc = L.ldp;
+    p.splits = L.splits;
+    LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DB, EPI_F32_SPLITK, true, true, p, st));
+    LOQT_HIP(launch_reduce_db(part, L.splits, r, in, L.ldp, dB, dB_dtype, ld_dB, accumulate, st));
+    return LOQT_OK;
+}
+
+loqt_status loqt_merge_nq(loqt_bf16* W, int64_t ld_W, const loqt_bf16* P, int64_t ld_P, const loqt_bf16* B,
+                          int64_t ld_B, int64_t out, int64_t in, int64_t r, float s, void* hip_stream) {
+    LOQT_TRY(check_layer_nq(W, ld_W, P, ld_P, B, ld_B, out, in, r));
+    GemmParams p;
+    memset(&p, 0, sizeof(p));  // W <- bf16(W + s P B), in place
+    p.A[0] = bf16_operand(P, ld_P, (int)out, (int)r);
+    p.B[0] = bf16_operand(B, ld_B, (int)in, (int)r);  // r x in: K x rows
+    p.M = (int)out;
+    p.N = (int)in;
+    p.alpha = s;
+    p.C = W;
+    p.ldc = ld_W;
+    p.w_bf16 = W;
+    p.w_bf16_ld = ld_W;
+    LOQT_HIP(launch_gemm_nt(SLOT_MERGE, EPI_ACC_BF16, false, true, p, (hipStream_t)hip_stream));
     return LOQT_OK;
 }
 

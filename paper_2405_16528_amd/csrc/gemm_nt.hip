@@ -283,7 +283,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     // ------------------------------------------------------------------ epilogues
     // accumulator tile (ti, tj): lane holds row m = ti*32 + (lane & 31); register 4*g + j holds
     // column n = tj*32 + 8*g + 4*(lane >> 5) + j.
-    if (EPI == EPI_BF16 || EPI == EPI_FOLD) {
+    if (EPI == EPI_BF16 || EPI == EPI_FOLD || EPI == EPI_ACC_BF16) {
         constexpr int EPITCH = Cfg::EPITCH, WTM = Cfg::WTM, WTN = Cfg::WTN;
         float* lut = reinterpret_cast<float*>(smem + Cfg::SMEM - 64);
         if (EPI == EPI_FOLD) {
@@ -313,6 +313,16 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 for (int g = 0; g < 4; ++g) {
                     float v0 = alpha * acc[ti][tj][4 * g + 0], v1 = alpha * acc[ti][tj][4 * g + 1];
                     float v2 = alpha * acc[ti][tj][4 * g + 2], v3 = alpha * acc[ti][tj][4 * g + 3];
+                    if (EPI == EPI_ACC_BF16) {
+                        // unquantised merge (M = out, N = in): add the old bf16 weight in fp32; the 8 bytes stay
+                        // inside the row's pitch (a multiple of 8 elements) even where n + 4 > N
+                        const int m = m0 + wm * WTM + ti * 32 + frow;
+                        const int n = n0 + wn * WTN + tj * 32 + 8 * g + 4 * h;
+                        if (m < p.M && n < N) {
+                            const uint2 o = *reinterpret_cast<const uint2*>(p.w_bf16 + (int64_t)m * p.w_bf16_ld + n);
+                            v0 += bf16_lo(o.x), v1 += bf16_hi(o.x), v2 += bf16_lo(o.y), v3 += bf16_hi(o.y);
+                        }
+                    }
                     if (EPI == EPI_FOLD) {
                         const uint32_t cw = (cw4[g] >> (16 * h)) & 0xffffu;
                         v0 += am * lut[nib4(cw, 0)];
@@ -540,7 +550,7 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     int choice = g_nt_tile_override;
     if (choice == 0) {
         const int K = p.A[0].K + p.A[1].K;
-        const bool light = (EPI == EPI_BF16 && K >= 2048) || EPI == EPI_FOLD;
+        const bool light = (EPI == EPI_BF16 && K >= 2048) || EPI == EPI_FOLD || EPI == EPI_ACC_BF16;
         choice = (light && tiles(256, 256) >= 224) ? 1 : 3;
     }
     if constexpr (EPI == EPI_BF16) {
@@ -595,6 +605,7 @@ hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmPar
             case EPI_FOLD: return launch_nt_sized<EPI_FOLD, false, true>(p, st);
             case EPI_COMP: return launch_nt_sized<EPI_COMP, false, true>(p, st);
             case EPI_FOLD_F32: return launch_nt_sized<EPI_FOLD_F32, false, true>(p, st);
+            case EPI_ACC_BF16: return launch_nt_sized<EPI_ACC_BF16, false, true>(p, st);
             default: break;
         }
     } else if (a_rc && b_rc) {

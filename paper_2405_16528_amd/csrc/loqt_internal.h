@@ -175,7 +175,7 @@ struct Operand {
     int K;                // extent along the contraction
 };
 
-enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3, EPI_COMP = 4, EPI_FOLD_F32 = 5 };
+enum Epilogue { EPI_BF16 = 0, EPI_F32_SPLITK = 1, EPI_MERGE = 2, EPI_FOLD = 3, EPI_COMP = 4, EPI_FOLD_F32 = 5, EPI_ACC_BF16 = 6 };
 
 struct GemmParams {
     Operand A[2], B[2];  // up to two K segments; segment 1 unused when A[1].K == 0
@@ -202,6 +202,9 @@ struct GemmParams {
     // EPI_COMP (M = out, N = in): W_hat = w_f32 + alpha * acc is quantised into out_codes / out_absmax
     // (pitch w_ld) and the residual w_f32 - deq(q(W_hat)) goes to e_out (bf16, pitch e_ld >= w_cols
     // rounded up to 64)
+    // EPI_ACC_BF16 (M = out, N = in): C = bf16(fp32(w_bf16) + alpha * acc); C may be w_bf16 itself
+    const uint16_t* w_bf16;
+    int64_t w_bf16_ld;
     const float* w_f32;
     int64_t w_f32_ld;
     uint16_t* e_out;

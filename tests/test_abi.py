@@ -26,7 +26,8 @@ def test_every_declared_symbol_is_exported(lib):
     assert {"nf4_quantize", "nf4_dequantize", "loqt_linear_fwd", "loqt_linear_bwd", "loqt_merge_requant",
             "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path",
             "loqt_init_compensate", "loqt_linear_fwd_right", "loqt_linear_bwd_right",
-            "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule"} <= names
+            "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule",
+            "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -55,7 +56,9 @@ def test_workspace_sizes(lib):
     assert ini >= out * r * 2 + out * inp * 2 + 2 * r * inp * 4 and ini % 256 == 0
     assert fwd % 256 == 0 and bwd % 256 == 0 and mrg % 256 == 0
     assert L.loqt_workspace_bytes(L.OP_FWD, 0, out, inp, r) == 0
-    assert L.loqt_workspace_bytes(7, T, out, inp, r) == 0
+    assert L.loqt_workspace_bytes(L.OP_FWD_NQ, T, out, inp, r) >= T * r * 2
+    assert L.loqt_workspace_bytes(L.OP_BWD_NQ, T, out, inp, r) >= T * r * 2 + 2 * r * inp * 4
+    assert L.loqt_workspace_bytes(99, T, out, inp, r) == 0
 
 
 def test_bad_arguments_are_rejected_before_launch(lib):
@@ -121,6 +124,14 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.loqt_adam_step(P, 512, 128, 512, None, 0, 512, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 1
     assert lib.loqt_merge_schedule(100.0, 1.2, 2500, 4, None) == 1
     assert lib.loqt_merge_schedule(100.0, 0.5, 2500, 0, (C.c_int64 * 1)()) == 1                            # psi < 1
+
+    assert lib.loqt_linear_fwd_nq(P, 512, 256, None, 512, P, 128, P, 512, 512, 512, 128, 1.0, P, 512, P, ws, None) == 1
+    assert lib.loqt_linear_fwd_nq(P, 512, 256, P, 500, P, 128, P, 512, 512, 512, 128, 1.0, P, 512, P, ws, None) == 2
+    assert lib.loqt_linear_fwd_nq(P, 512, 256, P, 512, P, 128, P, 512, 512, 512, 128, 1.0, P, 512, P, 16, None) == 4
+    assert lib.loqt_linear_bwd_nq(P, 512, P, 512, 256, P, 512, P, 128, P, 512, 512, 512, 128, 1.0, P, 512, None, 0,
+                                  512, 0, P, ws, None) == 1
+    assert lib.loqt_merge_nq(None, 512, P, 128, P, 512, 512, 512, 128, 1.0, None) == 1
+    assert lib.loqt_merge_nq(P, 512, P, 100, P, 512, 512, 512, 128, 1.0, None) == 2
 
     def init(W=P, ld_w=512, Pp=P, ld_p=128, out=512, inp=512, r=128, s=1.0, iters=3, warm=0, codes=P, am=P, ld_q=512,
              B=P, ld_B=512, w=P, wsb=ws):
