@@ -26,9 +26,9 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 METRIC = "LoQT NF4 linear fwd+bwd TFLOP/s at 7B shapes; merge+requant GB/s"
 
 # HBM-side traffic of the dominant kernel per launch, from profiles/bench_7b_block_hbm_traffic.md
-# per gemm_y launch slot: 256x256 kernel fetch 686.0 MB + write 98.1 MB, plus 2/7 of the 128x128 tail
+# per gemm_y launch slot: 256x256 kernel fetch 680.3 MB + write 98.1 MB, plus 2/7 of the 128x128 tail
 # launch of the gate and up projections (117.6 + 12.6 MB); null for workloads that were not profiled.
-TRAFFIC_BYTES_PER_LAUNCH = {"7b_block": 821.3e6}
+TRAFFIC_BYTES_PER_LAUNCH = {"7b_block": 815.6e6}
 
 
 def parse():
@@ -244,14 +244,26 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    L.timing_enable(True)
+    # the timed region: K steps, three events per step (start, after fwd+bwd, after merge), nothing else
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step(record=True)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # a second pass of K steps with the library's per-launch HIP events on the launch stream (the kernel
+    # breakdown and the roofline object come from here; the events cost about 2 % of the step, so they
+    # stay out of the region `value` is measured on)
+    timed_events = list(phase_events)
+    L.timing_enable(True)
+    t2 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
     L.timing_enable(False)
     kt = L.timing_read()
+    phase_events = timed_events
+    ms_step_instrumented = (t3 - t2) * 1e3 / args.steps
 
     ms_step = (t1 - t0) * 1e3 / args.steps
     f_fb = sum(synth.flops_fwd(T, o, i, r) + synth.flops_bwd(T, o, i, r) for (_, o, i) in wl.projections)
@@ -302,16 +314,13 @@ def main():
         # see profiles/bench_7b_block_hbm_traffic.md; not measurable from inside this process
         "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(wl.name),
     }
-    # the merge is bound by max(HBM stream, rank-r bf16 product); report both views
-    mk = kernels.get("merge_requant")
-    merge = None
-    if mk:
-        t_hbm = b_mg / (PEAK_HBM_GBS * 1e9) * 1e3
-        t_mfma = f_mg / (PEAK_BF16_TFLOPS * 1e12) * 1e3
-        merge = {"ms_per_step": mk["ms_per_step"], "algorithmic_GBs": b_mg / (mk["ms_per_step"] * 1e-3) / 1e9,
-                 "tflops": mk["tflops"], "t_hbm_ms": t_hbm, "t_mfma_ms": t_mfma,
-                 "frac_of_binding_roof": max(t_hbm, t_mfma) / mk["ms_per_step"],
-                 "frac_of_hbm_peak": t_hbm / mk["ms_per_step"]}
+    # the merge is bound by max(HBM stream, rank-r bf16 product); report both views.  Time: the whole
+    # loqt_merge_requant_batched call of the timed region (pre-pass of P included), not the kernel slot alone
+    t_hbm = b_mg / (PEAK_HBM_GBS * 1e9) * 1e3
+    t_mfma = f_mg / (PEAK_BF16_TFLOPS * 1e12) * 1e3
+    merge = {"ms_per_step": ms_mg, "algorithmic_GBs": b_mg / (ms_mg * 1e-3) / 1e9,
+             "tflops": f_mg / (ms_mg * 1e-3) / 1e12, "t_hbm_ms": t_hbm, "t_mfma_ms": t_mfma,
+             "frac_of_binding_roof": max(t_hbm, t_mfma) / ms_mg, "frac_of_hbm_peak": t_hbm / ms_mg}
 
     out = {
         "metric": METRIC,
@@ -331,6 +340,9 @@ def main():
                     "frac_of_bf16_peak": f_fb / (ms_fb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         "merge": merge,
         "kernels": kernels,
+        "kernels_pass": {"steps": args.steps, "ms_per_step": ms_step_instrumented,
+                         "note": "per-kernel figures and the roofline object: a second pass of the same K steps "
+                                 "with a HIP event pair around every launch"},
         "roofline": roofline,
     }
     if not args.no_extras:
