@@ -316,8 +316,9 @@ loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int6
  *                      y = x W_eff^T and dx = dy W_eff.  The intermediate U is not formed; Z still is
  *                      (dB = Z^T x).  Cheaper than carrying the rank-r term through every token
  *                      (2 T r (in + out) flop per pass) from T = out in / (in + out) tokens up.
- *   LOQT_PATH_AUTO   : fused below 1024 rows (tokens; `in` for the merge) per weight tile, else
- *                      pre-pass; folded when T (in + out) >= 2 out in.
+ *   LOQT_PATH_AUTO   : forward and backward always take the pre-pass family (measured ahead of the
+ *                      fused form at every token count from 16 up), folded when T (in + out) >= out in;
+ *                      the merge is fused below 1024 columns (`in`), pre-pass above.
  * All compute the same quantities; results differ only in rounding order, within the stated
  * tolerance.
  */
