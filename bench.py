@@ -38,6 +38,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="7b_block")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--mode", choices=["saved", "plain"], default="saved",
+                    help="saved: forward of all projections with loqt_linear_fwd_save, then backward in reverse order "
+                         "with loqt_linear_bwd_saved (the transient bf16 weight of each layer is kept in between, "
+                         "one fold per layer and step); plain: loqt_linear_fwd + loqt_linear_bwd layer by layer "
+                         "(nothing kept, the weight is folded in both passes).  The other mode is timed too and "
+                         "reported beside the headline.")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=8192)
     ap.add_argument("--no-extras", action="store_true",
@@ -215,19 +221,29 @@ def main():
                        L.loqt_workspace_bytes(L.OP_FWD, T, out, inp, r),
                        L.loqt_workspace_bytes(L.OP_MERGE, T, out, inp, r))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    for l in layers:  # the transient bf16 weight of the saved mode: out x in per layer (0.4 GB for the 7B block)
+        l["w_eff"] = torch.empty((l["out"], pitch8(l["inp"])), dtype=torch.bfloat16, device=dev)[:, :l["inp"]]
     descs = L.make_merge_descs([(l["Wq"], l["Wq_out"], l["Pq"], l["B"], 1.0) for l in layers])
     torch.cuda.synchronize()
 
     ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
     phase_events = []
 
+    mode = args.mode
+
     def step(record=False):
         if record:
             e0, e1, e2 = ev(), ev(), ev()
             e0.record()
-        for l in layers:
-            L.loqt_linear_fwd(l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["y"], ws)
-            L.loqt_linear_bwd(l["dy"], l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["dx"], l["dB"], False, ws)
+        if mode == "saved":
+            for l in layers:
+                L.loqt_linear_fwd_save(l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["y"], l["w_eff"], ws)
+            for l in reversed(layers):
+                L.loqt_linear_bwd_saved(l["dy"], l["x"], l["Pq"], 1.0, l["w_eff"], l["dx"], l["dB"], False, ws)
+        else:
+            for l in layers:
+                L.loqt_linear_fwd(l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["y"], ws)
+                L.loqt_linear_bwd(l["dy"], l["x"], l["Wq"], l["Pq"], l["B"], 1.0, l["dx"], l["dB"], False, ws)
         if record:
             e1.record()
         L.loqt_merge_requant_batched(descs, ws)
@@ -262,6 +278,18 @@ def main():
     t3 = time.perf_counter()
     L.timing_enable(False)
     kt = L.timing_read()
+    # the other mode, timed the same way as the headline (reported beside it, not part of `value`)
+    other = "plain" if args.mode == "saved" else "saved"
+    mode, phase_events = other, []
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t4 = time.perf_counter()
+    for _ in range(args.steps):
+        step(record=True)
+    torch.cuda.synchronize()
+    t5 = time.perf_counter()
+    other_events, mode = phase_events, args.mode
     phase_events = timed_events
     ms_step_instrumented = (t3 - t2) * 1e3 / args.steps
 
@@ -273,7 +301,8 @@ def main():
     ms_mg = sum(b.elapsed_time(c) for (_, b, c) in phase_events) / args.steps
 
     # flops each kernel actually executes over one step (depends on the implementation the library picks)
-    folded = {n: L.resolved_path(L.OP_FWD, T, o, i) == L.PATH_FOLDED for (n, o, i) in wl.projections}
+    saved = args.mode == "saved"
+    folded = {n: saved or L.resolved_path(L.OP_FWD, T, o, i) == L.PATH_FOLDED for (n, o, i) in wl.projections}
     kflops = {
         "gemm_u": sum(2 * T * i * r for (n, o, i) in wl.projections if not folded[n]),
         "gemm_y": sum(2 * T * o * (i + (0 if folded[n] else r)) for (n, o, i) in wl.projections),
@@ -281,7 +310,7 @@ def main():
         "gemm_z+dx": sum(2 * T * o * (i + r) if folded[n] else 2 * T * (o * r + i * (o + r))
                          for (n, o, i) in wl.projections),
         "gemm_db": sum(2 * T * r * i for (n, o, i) in wl.projections),
-        "fold_weight": sum(2 * 2 * o * i * r for (n, o, i) in wl.projections if folded[n]),
+        "fold_weight": sum((1 if saved else 2) * 2 * o * i * r for (n, o, i) in wl.projections if folded[n]),
         "merge_requant": f_mg,
     }
     f_exec = sum(v for k, v in kflops.items() if k != "merge_requant")
@@ -331,14 +360,24 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "tokens": T, "rank": r,
                    "projections": [f"{n}:{o}x{i}" for (n, o, i) in wl.projections],
-                   "step": "7x(loqt_linear_fwd + loqt_linear_bwd) + batched merge/requant of the block"},
+                   "mode": args.mode,
+                   "step": ("loqt_linear_fwd_save of the 7 projections, loqt_linear_bwd_saved of the 7 in reverse order "
+                            "(W_eff bf16 kept per layer in between: %.2f GB), batched merge/requant of the block"
+                            % (sum(o * pitch8(i) for (_, o, i) in wl.projections) * 2 / 1e9)) if saved else
+                           "7x(loqt_linear_fwd + loqt_linear_bwd) + batched merge/requant of the block"},
         "fwd_bwd": {"tflops": f_fb / (ms_fb * 1e-3) / 1e12, "ms_per_step": ms_fb,
                     "flop_model": "algorithmic, factored form: fwd 2T(out*in + in*r + r*out), bwd 2T(out*in + out*r + 2*r*in)",
                     "executed_tflops": f_exec / (ms_fb * 1e-3) / 1e12,
-                    "paths": sorted({["auto", "fused", "prepass", "folded"][L.resolved_path(L.OP_FWD, T, o, i)]
+                    "paths": ["folded"] if saved else
+                             sorted({["auto", "fused", "prepass", "folded"][L.resolved_path(L.OP_FWD, T, o, i)]
                                      for (_, o, i) in wl.projections}),
                     "frac_of_bf16_peak": f_fb / (ms_fb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
         "merge": merge,
+        "other_mode": {"mode": other, "ms_per_step": (t5 - t4) * 1e3 / args.steps,
+                       "value": (f_fb + f_mg) / ((t5 - t4) / args.steps) / 1e12,
+                       "fwd_bwd_ms_per_step": sum(a.elapsed_time(b) for (a, b, _) in other_events) / args.steps,
+                       "fwd_bwd_tflops": f_fb / (sum(a.elapsed_time(b) for (a, b, _) in other_events) / args.steps
+                                                 * 1e-3) / 1e12},
         "kernels": kernels,
         "kernels_pass": {"steps": args.steps, "ms_per_step": ms_step_instrumented,
                          "note": "per-kernel figures and the roofline object: a second pass of the same K steps "

@@ -150,6 +150,31 @@ loqt_status loqt_linear_bwd(const loqt_bf16 *dy, int64_t ld_dy, const loqt_bf16 
                             void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * loqt_linear_fwd_save / loqt_linear_bwd_saved -- the same forward and backward pass (sec. 2.2, 2.4)
+ * for callers that can afford to keep the transient 16-bit weight between the two: the forward call
+ * also leaves
+ *   W_eff[out x in] = bf16( fl32(deq(Wq)) + s * deq(Pq) B )          (w_eff, pitch ld_weff, caller-owned)
+ * and the backward call takes it back instead of rebuilding it from the 4-bit codes:
+ *   Z = s * dy deq(Pq),  dx = dy W_eff,  dB = Z^T x.
+ * y, dx and dB are those of the two calls above when they run the folded form (same kernels, same
+ * bits).  w_eff must hold out rows of ld_weff >= in elements (ld_weff % 8 == 0, 16-byte aligned) and
+ * must not be touched between the two calls; `in` tells the backward call its width.  Any number of
+ * forward / backward pairs may reuse one w_eff while Wq, Pq, B and s stay the same (the micro-batches
+ * of a gradient-accumulation step, sec. 3.3).  Workspace sizes are those of LOQT_OP_FWD / LOQT_OP_BWD.
+ */
+loqt_status loqt_linear_fwd_save(const loqt_bf16 *x, int64_t ld_x, int64_t T,
+                                 const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq,
+                                 const loqt_bf16 *B, int64_t ld_B, float s,
+                                 loqt_bf16 *y, int64_t ld_y, loqt_bf16 *w_eff, int64_t ld_weff,
+                                 void *ws, size_t ws_bytes, void *hip_stream);
+loqt_status loqt_linear_bwd_saved(const loqt_bf16 *dy, int64_t ld_dy, const loqt_bf16 *x, int64_t ld_x,
+                                  int64_t T, const loqt_nf4_mat *Pq, int64_t in, float s,
+                                  const loqt_bf16 *w_eff, int64_t ld_weff,
+                                  loqt_bf16 *dx, int64_t ld_dx,
+                                  void *dB, int dB_dtype, int64_t ld_dB, int accumulate,
+                                  void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * loqt_merge_requant -- the periodic merge (Alg. 1 line 5; sec. 2.4: dequantise W_q and P_q,
  * add P B, quantise again, one layer at a time).
  *   W_new = deq(Wq) + s * deq(Pq) B   (fp32: fl32(M*q) + fp32-accumulated bf16 product)

@@ -61,6 +61,12 @@ lib.loqt_linear_fwd.argtypes = [_vp, _i64, _i64, _P(NF4MatC), _P(NF4MatC), _vp, 
 lib.loqt_linear_bwd.restype = _i
 lib.loqt_linear_bwd.argtypes = [_vp, _i64, _vp, _i64, _i64, _P(NF4MatC), _P(NF4MatC), _vp, _i64, _f,
                                 _vp, _i64, _vp, _i, _i64, _i, _vp, _sz, _vp]
+lib.loqt_linear_fwd_save.restype = _i
+lib.loqt_linear_fwd_save.argtypes = [_vp, _i64, _i64, _P(NF4MatC), _P(NF4MatC), _vp, _i64, _f, _vp, _i64, _vp, _i64,
+                                     _vp, _sz, _vp]
+lib.loqt_linear_bwd_saved.restype = _i
+lib.loqt_linear_bwd_saved.argtypes = [_vp, _i64, _vp, _i64, _i64, _P(NF4MatC), _i64, _f, _vp, _i64,
+                                      _vp, _i64, _vp, _i, _i64, _i, _vp, _sz, _vp]
 lib.loqt_merge_requant.restype = _i
 lib.loqt_merge_requant.argtypes = [_P(NF4MatC), _vp, _vp, _P(NF4MatC), _vp, _i64, _f, _vp, _sz, _vp]
 lib.loqt_merge_requant_batched.restype = _i
@@ -175,6 +181,24 @@ def loqt_linear_bwd(dy, x, Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, dx, dB, ac
                                _pitch(dx) if dx is not None else 0, dB.data_ptr(), dt, _pitch(dB),
                                1 if accumulate else 0, _ptr(ws), ws.numel() * ws.element_size(), _stream()),
            "loqt_linear_bwd")
+    return dx, dB
+
+
+def loqt_linear_fwd_save(x, Wq: NF4Tensor, Pq: NF4Tensor, B, s: float, y, w_eff, ws) -> torch.Tensor:
+    """Forward pass that also leaves the transient bf16 weight in w_eff (out, >= in) for loqt_linear_bwd_saved."""
+    _check(lib.loqt_linear_fwd_save(x.data_ptr(), _pitch(x), x.shape[0], C.byref(Wq.c()), C.byref(Pq.c()),
+                                    B.data_ptr(), _pitch(B), s, y.data_ptr(), _pitch(y), w_eff.data_ptr(),
+                                    _pitch(w_eff), *_ws_args(ws), _stream()), "loqt_linear_fwd_save")
+    return y
+
+
+def loqt_linear_bwd_saved(dy, x, Pq: NF4Tensor, s: float, w_eff, dx, dB, accumulate: bool, ws):
+    """Backward pass from the weight loqt_linear_fwd_save left behind; dx may be None."""
+    dt = {torch.float32: F32, torch.bfloat16: BF16}[dB.dtype]
+    _check(lib.loqt_linear_bwd_saved(dy.data_ptr(), _pitch(dy), x.data_ptr(), _pitch(x), x.shape[0], C.byref(Pq.c()),
+                                     x.shape[1], s, w_eff.data_ptr(), _pitch(w_eff), _ptr(dx),
+                                     _pitch(dx) if dx is not None else 0, dB.data_ptr(), dt, _pitch(dB),
+                                     1 if accumulate else 0, *_ws_args(ws), _stream()), "loqt_linear_bwd_saved")
     return dx, dB
 
 

@@ -419,9 +419,12 @@ size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t 
     }
 }
 
-loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_nf4_mat* Wq,
-                            const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
-                            loqt_bf16* y, int64_t ld_y, void* ws, size_t ws_bytes, void* hip_stream) {
+// save_weff != NULL: the folded form is used whatever the path option says and W_eff goes to the caller's
+// buffer (pitch ld_save) instead of the workspace
+static loqt_status fwd_impl(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_nf4_mat* Wq,
+                            const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, loqt_bf16* y,
+                            int64_t ld_y, loqt_bf16* save_weff, int64_t ld_save, void* ws, size_t ws_bytes,
+                            void* hip_stream) {
     LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
     const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
     LOQT_TRY(check_bf16(x, T, in, ld_x));
@@ -434,13 +437,14 @@ loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
     loqt_bf16* U = reinterpret_cast<loqt_bf16*>(ws);
     GemmParams p;
 
-    if (use_prepass(T)) {
+    if (save_weff) LOQT_TRY(check_bf16(save_weff, out, in, ld_save));
+    if (save_weff || use_prepass(T)) {
         const FwdWs L(T, out, in, r);
         char* base = reinterpret_cast<char*>(ws);
-        uint16_t* Wb = reinterpret_cast<uint16_t*>(base + L.Wb);
+        uint16_t* Wb = save_weff ? save_weff : reinterpret_cast<uint16_t*>(base + L.Wb);
         uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
-        const int64_t ldw = (int64_t)round_up(in, 8);
-        const bool folded = use_folded(T, out, in);
+        const int64_t ldw = save_weff ? ld_save : (int64_t)round_up(in, 8);
+        const bool folded = save_weff || use_folded(T, out, in);
         if (folded) {
             // y = x W_eff^T with W_eff = deq(W) + s deq(P) B folded once per call
             LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, Wb, ldw, true, st));
@@ -500,12 +504,35 @@ loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
     return LOQT_OK;
 }
 
-loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
+loqt_status loqt_linear_fwd(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_nf4_mat* Wq,
+                            const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s,
+                            loqt_bf16* y, int64_t ld_y, void* ws, size_t ws_bytes, void* hip_stream) {
+    return fwd_impl(x, ld_x, T, Wq, Pq, B, ld_B, s, y, ld_y, nullptr, 0, ws, ws_bytes, hip_stream);
+}
+
+loqt_status loqt_linear_fwd_save(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_nf4_mat* Wq,
+                                 const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B, float s, loqt_bf16* y,
+                                 int64_t ld_y, loqt_bf16* w_eff, int64_t ld_weff, void* ws, size_t ws_bytes,
+                                 void* hip_stream) {
+    if (!w_eff) return LOQT_INVALID_ARG;
+    return fwd_impl(x, ld_x, T, Wq, Pq, B, ld_B, s, y, ld_y, w_eff, ld_weff, ws, ws_bytes, hip_stream);
+}
+
+// saved != NULL: W_eff (out x in_saved, bf16, pitch ld_saved) was produced by loqt_linear_fwd_save with the same
+// W_q, P_q, B and s; it replaces the fold, and Wq / B are not looked at
+static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
                             const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B,
                             float s, loqt_bf16* dx, int64_t ld_dx, void* dB, int dB_dtype, int64_t ld_dB,
-                            int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
-    LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
-    const int64_t out = Wq->rows, in = Wq->cols, r = Pq->cols;
+                            int accumulate, const loqt_bf16* saved, int64_t ld_saved, int64_t in_saved, void* ws,
+                            size_t ws_bytes, void* hip_stream) {
+    if (saved) {
+        LOQT_TRY(check_nf4(Pq));
+        if (in_saved < 0) return LOQT_INVALID_ARG;
+        LOQT_TRY(check_bf16(saved, Pq->rows, in_saved, ld_saved));
+    } else {
+        LOQT_TRY(check_layer(Wq, Pq, B, ld_B));
+    }
+    const int64_t out = Pq->rows, in = saved ? in_saved : Wq->cols, r = Pq->cols;
     LOQT_TRY(check_bf16(dy, T, out, ld_dy));
     LOQT_TRY(check_bf16(x, T, in, ld_x));
     if (dx) LOQT_TRY(check_bf16(dx, T, in, ld_dx));
@@ -522,15 +549,15 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
     float* partials = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + bwd_z_bytes(T, r));
 
     GemmParams p;
-    if (use_prepass(T)) {
+    if (saved || use_prepass(T)) {
         const BwdWs L(T, out, in, r);
         char* base = reinterpret_cast<char*>(ws);
-        uint16_t* Wb = reinterpret_cast<uint16_t*>(base + L.Wb);
+        const uint16_t* Wb = saved ? saved : reinterpret_cast<const uint16_t*>(base + L.Wb);
         uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
         float* part = reinterpret_cast<float*>(base + L.partials);
-        const int64_t ldw = (int64_t)round_up(in, 8);
+        const int64_t ldw = saved ? ld_saved : (int64_t)round_up(in, 8);
         LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_z, st, SLOT_PREPASS));
-        const bool folded = dx && use_folded(T, out, in);
+        const bool folded = dx && (saved || use_folded(T, out, in));
         // Z rides along with dx (one product [dx | Z] over the shared operand dy) when its tiles fit
         // into the last, partly empty round of 256x256 tiles of the dx product; otherwise its own launch
         bool z_with_dx = false;
@@ -553,10 +580,11 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
         }
         if (dx) {
             // dx = dy Wb (+ Z B when the rank-r term is not folded into Wb); Wb is out x in: K x rows
+            uint16_t* Wws = reinterpret_cast<uint16_t*>(base + L.Wb);
             if (folded) {
-                LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, Wb, ldw, false, st));
+                if (!saved) LOQT_TRY(fold_weight(Wq, Pq, B, ld_B, s, Pb, Wws, ldw, false, st));
             } else {
-                LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wb, LOQT_BF16, ldw, st,
+                LOQT_HIP(launch_dequantize(Wq->codes, Wq->absmax, out, in, Wq->ld, Wws, LOQT_BF16, ldw, st,
                                            SLOT_PREPASS));
             }
             memset(&p, 0, sizeof(p));
@@ -630,6 +658,23 @@ loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
     LOQT_HIP(launch_gemm(GEMM_DB, p, st));
     LOQT_HIP(launch_reduce_db(partials, p.splits, r, in, in, dB, dB_dtype, ld_dB, accumulate, st));
     return LOQT_OK;
+}
+
+loqt_status loqt_linear_bwd(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
+                            const loqt_nf4_mat* Wq, const loqt_nf4_mat* Pq, const loqt_bf16* B, int64_t ld_B,
+                            float s, loqt_bf16* dx, int64_t ld_dx, void* dB, int dB_dtype, int64_t ld_dB,
+                            int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+    return bwd_impl(dy, ld_dy, x, ld_x, T, Wq, Pq, B, ld_B, s, dx, ld_dx, dB, dB_dtype, ld_dB, accumulate, nullptr,
+                    0, 0, ws, ws_bytes, hip_stream);
+}
+
+loqt_status loqt_linear_bwd_saved(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16* x, int64_t ld_x, int64_t T,
+                                  const loqt_nf4_mat* Pq, int64_t in, float s, const loqt_bf16* w_eff,
+                                  int64_t ld_weff, loqt_bf16* dx, int64_t ld_dx, void* dB, int dB_dtype,
+                                  int64_t ld_dB, int accumulate, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!w_eff) return LOQT_INVALID_ARG;
+    return bwd_impl(dy, ld_dy, x, ld_x, T, nullptr, Pq, nullptr, 0, s, dx, ld_dx, dB, dB_dtype, ld_dB, accumulate,
+                    w_eff, ld_weff, in, ws, ws_bytes, hip_stream);
 }
 
 loqt_status loqt_merge_requant(const loqt_nf4_mat* Wq, uint8_t* codes_out, float* absmax_out,

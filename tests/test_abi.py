@@ -27,7 +27,8 @@ def test_every_declared_symbol_is_exported(lib):
             "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path",
             "loqt_init_compensate", "loqt_linear_fwd_right", "loqt_linear_bwd_right",
             "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule",
-            "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq"} <= names
+            "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq", "loqt_linear_fwd_save",
+            "loqt_linear_bwd_saved"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -93,6 +94,18 @@ def test_bad_arguments_are_rejected_before_launch(lib):
                                P, ws, None) == 1                                       # unknown dB dtype
     assert lib.loqt_linear_bwd(P, 512, P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 0, 100, 0,
                                P, ws, None) == 2                                       # ld_dB < in
+    # the pair that keeps the transient 16-bit weight between forward and backward
+    fs, bs = lib.loqt_linear_fwd_save, lib.loqt_linear_bwd_saved
+    assert fs(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, None, 512, P, ws, None) == 1   # no w_eff
+    assert fs(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 508, P, ws, None) == 2      # pitch < in
+    assert fs(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P + 8, 512, P, ws, None) == 3  # misaligned
+    assert fs(P, 512, 256, C.byref(W), C.byref(Pm), P, 512, 1.0, P, 512, P, 512, P, 16, None) == 4
+    assert bs(P, 512, P, 512, 256, C.byref(Pm), 512, 1.0, None, 512, P, 512, P, 0, 512, 0, P, ws, None) == 1
+    assert bs(P, 512, P, 512, 256, None, 512, 1.0, P, 512, P, 512, P, 0, 512, 0, P, ws, None) == 1      # no P_q
+    assert bs(P, 512, P, 512, 256, C.byref(Pm), -4, 1.0, P, 512, P, 512, P, 0, 512, 0, P, ws, None) == 1
+    assert bs(P, 512, P, 512, 256, C.byref(Pm), 512, 1.0, P, 500, P, 512, P, 0, 512, 0, P, ws, None) == 2  # pitch < in
+    assert bs(P, 512, P, 512, 256, C.byref(Pm), 512, 1.0, P, 512, P, 512, None, 0, 512, 0, P, ws, None) == 1  # no dB
+    assert bs(P, 512, P, 512, 256, C.byref(Pm), 512, 1.0, P, 512, P, 512, P, 0, 512, 0, P, 16, None) == 4
     assert lib.loqt_merge_requant(C.byref(W), None, P, C.byref(Pm), P, 512, 1.0, P, ws, None) == 1
     assert lib.loqt_merge_requant(C.byref(W), P + 64, P, C.byref(Pm), P, 512, 1.0, P, ws, None) == 1  # partial overlap
     assert lib.loqt_merge_requant_batched(-1, None, P, ws, None) == 1
