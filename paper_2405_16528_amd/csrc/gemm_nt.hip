@@ -9,14 +9,18 @@
 //
 // Work-group: 256 threads = 4 waves (2 x 2), tile BM x BN x 64, v_mfma_f32_32x32x16_bf16.
 //  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
-//    registers, no ds_write); two LDS stages, the loads of tile t+2 are issued as soon as the
-//    barrier of tile t has released its stage, so they have a whole tile of MFMAs to land;
+//    registers, no ds_write); two LDS stages.  When every K segment is a whole number of k-tiles
+//    the loads of a tile are issued one by one between the MFMAs, half of them in the k16 step
+//    right after the barrier that frees the stage and half in the next one, so the matrix cores
+//    never wait for a burst of loads and every load has half a tile of MFMAs or more to land;
+//    the general loop (K tails) issues a tile's loads in one piece after that barrier;
 //  * 16-byte chunks of an LDS row are XOR-swizzled; the swizzle is applied on the global side
 //    (which chunk a lane fetches), the LDS side of a direct load is lane-linear;
 //  * K-contiguous tiles are read back with one 16-byte read per fragment, row-contiguous tiles
 //    with two transposing reads (ds_read_b64_tr_b16): no operand is ever transposed in memory;
 //  * MFMA fragments are double-buffered in registers one k16 step ahead, reads interleaved
-//    one-to-one with the MFMAs of the running step (sched_group_barrier);
+//    one-to-one with the MFMAs of the running step (a scheduling fence after every MFMA slot
+//    in the whole-tile loop, sched_group_barrier in the general one);
 //  * the accumulators are kept transposed (lane = row m, registers = 4 consecutive n) so the
 //    epilogues can pack along n: bf16 results are staged through LDS and leave as whole
 //    16-byte-per-lane row segments; the fold epilogue adds the dequantised NF4 weight on the way;
@@ -48,6 +52,18 @@ constexpr int ROWB = 128;  // bytes of one LDS row (64 bf16)
         __builtin_amdgcn_sched_barrier(0);                               \
     } while (0)
 
+// the same for a k16 step that also carries NL direct loads: reads on the first MFMAs, loads on the last
+// ones (DPS reads on each of the first NRS MFMAs, LPS loads on each of the last NSL)
+#define LOQT_SCHED_GROUP_LD()                                                        \
+    do {                                                                             \
+        _Pragma("unroll") for (int q_ = 0; q_ < NM; ++q_) {                          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       \
+            if (q_ < NRS) __builtin_amdgcn_sched_group_barrier(0x100, DPS, 0);       \
+            if (q_ >= NM - NSL) __builtin_amdgcn_sched_group_barrier(0x020, LPS, 0); \
+        }                                                                            \
+        __builtin_amdgcn_sched_barrier(0);                                           \
+    } while (0)
+
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 __device__ __forceinline__ uint32_t nib4(uint32_t word, int e) {
@@ -62,21 +78,27 @@ struct NtCfg {
     static constexpr int STAGE = (BM + BN) * ROWB;
     static constexpr int NCH = (BM + BN) / 32;         // 16-byte chunks per thread per stage
     static constexpr int NCHA = BM / 32;               // of which belong to A
+    static constexpr int NCHB = BN / 32;               // and to B
     static constexpr int EPITCH = WTN * 2 + 8;         // staging pitch of the bf16 epilogue
     static constexpr int SMEM_MAIN = 2 * STAGE;
     static constexpr int SMEM_EPI = 4 * WTM * EPITCH;
     static constexpr int SMEM = (SMEM_MAIN > SMEM_EPI ? SMEM_MAIN : SMEM_EPI) + 64;
 };
 
-template <int BM, int BN, int EPI, bool ARC, bool BRC>
+// KTAIL = false: every K segment is a whole number of k-tiles (the host checks); the main loop then has no
+// branch around its loads and spreads them between the MFMAs.  KTAIL = true: the general loop.
+template <int BM, int BN, int EPI, bool ARC, bool BRC, bool KTAIL>
 __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     using Cfg = NtCfg<BM, BN>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE;
     constexpr int NM = TM * TN, NR = TM * (ARC ? 2 : 1) + TN * (BRC ? 2 : 1);  // MFMAs / LDS reads per k16 step
+    constexpr int NL = Cfg::NCH / 2;                                           // direct loads of half a k-tile
+    constexpr int DPS = (NR + NM - 1) / NM, NRS = (NR + DPS - 1) / DPS, LPS = (NL + NM - 1) / NM, NSL = NL / LPS;
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
 
     // ---- tile of this work-group: contiguous range per XCD, 8-row groups inside
     const int tiles_m = (p.M + BM - 1) / BM;
@@ -254,29 +276,188 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
     };
 
-    if (kt_begin < kt_end) {
-        stage_tile(kt_begin, smem);
-        __syncthreads();  // waits for the direct loads (vmcnt) and the tail writes (lgkmcnt)
-        load_frags(smem, 0, 0);
-        if (kt_begin + 1 < kt_end) stage_tile(kt_begin + 1, smem + STAGE);
-    }
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
-        char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
-        load_frags(cur, 1, 1);
-        mfmas(0);
-        LOQT_SCHED_GROUP();
-        load_frags(cur, 2, 0);
-        mfmas(1);
-        LOQT_SCHED_GROUP();
-        load_frags(cur, 3, 1);
-        mfmas(0);
-        LOQT_SCHED_GROUP();
-        __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
-        load_frags(nxt, 0, 0);   // (harmless stale read after the last tile)
-        if (kt + 2 < kt_end) stage_tile(kt + 2, cur);
-        mfmas(1);
-        LOQT_SCHED_GROUP();
+    if constexpr (KTAIL) {
+        if (kt_begin < kt_end) {
+            stage_tile(kt_begin, smem);
+            __syncthreads();  // waits for the direct loads (vmcnt) and the tail writes (lgkmcnt)
+            load_frags(smem, 0, 0);
+            if (kt_begin + 1 < kt_end) stage_tile(kt_begin + 1, smem + STAGE);
+        }
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
+            char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
+            load_frags(cur, 1, 1);
+            mfmas(0);
+            LOQT_SCHED_GROUP();
+            load_frags(cur, 2, 0);
+            mfmas(1);
+            LOQT_SCHED_GROUP();
+            load_frags(cur, 3, 1);
+            mfmas(0);
+            LOQT_SCHED_GROUP();
+            __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
+            load_frags(nxt, 0, 0);   // (harmless stale read after the last tile)
+            if (kt + 2 < kt_end) stage_tile(kt + 2, cur);
+            mfmas(1);
+            LOQT_SCHED_GROUP();
+        }
+    } else {
+        // Whole k-tiles only.  The lane offsets of a thread's chunks are loop-invariant registers (per K segment)
+        // and the tile origin is a scalar pointer that advances by a constant, so a load is one instruction plus
+        // scalar bookkeeping and can sit between the MFMAs.  A k-tile is issued in two halves: the first during
+        // the last k16 step of the tile two before it (right after the barrier that frees its stage), the second
+        // during the first k16 step of the tile before it; the two k16 steps in between carry no loads, so
+        // every load has at least half a k-tile of MFMAs to land before the barrier that publishes it.
+        uint32_t offA[Cfg::NCHA], offB[Cfg::NCHB];
+        const char *hotA = nullptr, *hotB = nullptr;  // operand bytes of the tile whose first half was issued last
+        int64_t stepA = 0, stepB = 0;
+        auto hot_operand = [&](auto rc_tag, auto br_tag, const void* optr, int64_t old, int orows, int row0, int k0,
+                               uint32_t* off, const char*& base, int64_t& step) {
+            constexpr bool RC = decltype(rc_tag)::value;
+            constexpr int BR = decltype(br_tag)::value;
+            constexpr int NC = BR / 32;
+            if (row0 >= orows) row0 = 0;  // as in stage_operand
+            const uint32_t ld2 = (uint32_t)old * 2u;
+            if constexpr (!RC) {
+                const int r0 = tid >> 3;
+                const int kc = (tid & 7) ^ swz(r0);
+                const int rlast = orows - 1 - row0;
+#pragma unroll
+                for (int i = 0; i < NC; ++i) off[i] = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
+                base = reinterpret_cast<const char*>(optr) + ((int64_t)row0 * old + k0) * 2;
+                step = BK * 2;
+            } else {
+                constexpr int CPR = BR / 8;
+                constexpr int KPI = 256 / CPR;
+                const int kq = tid / CPR;
+                const int logical = (tid % CPR) ^ (4 * (kq & 3));
+                const int clast = (((orows - 1) >> 3) << 3) - row0;
+#pragma unroll
+                for (int i = 0; i < NC; ++i)
+                    off[i] = (uint32_t)(kq + i * KPI) * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
+                base = reinterpret_cast<const char*>(optr) + ((int64_t)k0 * old + row0) * 2;
+                step = (int64_t)BK * old * 2;
+            }
+        };
+        auto hot_setup = [&](int kt) {  // kt: a tile of the range
+            const bool seg = kt >= nkt0;
+            const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
+            // field-by-field selects keep everything in scalar registers (a run-time index into the by-value
+            // parameter block, or a copy of an Operand, would go through scratch memory)
+            const void* aptr = seg ? p.A[1].ptr : p.A[0].ptr;
+            const int64_t ald = seg ? p.A[1].ld : p.A[0].ld;
+            const int arows = seg ? p.A[1].rows : p.A[0].rows;
+            const void* bptr = part1 ? p.Bx.ptr : (seg ? p.B[1].ptr : p.B[0].ptr);
+            const int64_t bld = part1 ? p.Bx.ld : (seg ? p.B[1].ld : p.B[0].ld);
+            const int brows = part1 ? p.Bx.rows : (seg ? p.B[1].rows : p.B[0].rows);
+            hot_operand(std::integral_constant<bool, ARC>{}, std::integral_constant<int, BM>{}, aptr, ald, arows, m0, k0, offA,
+                        hotA, stepA);
+            hot_operand(std::integral_constant<bool, BRC>{}, std::integral_constant<int, BN>{}, bptr, bld, brows, n0, k0, offB,
+                        hotB, stepB);
+        };
+        auto hot_advance = [&](int kt) {  // move on to tile kt, the successor of the current one (kt < kt_end)
+            if (kt == nkt0) hot_setup(kt);
+            else hotA += stepA, hotB += stepB;
+        };
+        const uint32_t lds0 = (uint32_t)(uintptr_t)LOQT_LDS_PTR(smem);
+        // Load n of half H (0: first half of the chunks of A then of B, 1: second half, 2: all) into `stage`.
+        // The direct load is inline assembly for two reasons.  (1) The compiler cannot tell that the LDS reads of
+        // the running tile never touch the stage the loads in flight are writing, and would wait for all of
+        // them (vmcnt(0)) before every group of transposing reads; written this way it does not see them, and the
+        // loop waits for them itself before each barrier.  (2) `live` (wave-uniform, all ones or zero) goes into
+        // both halves of EXEC for the one instruction, so the loads past the end of the range are switched off without a
+        // second copy of the loop body.  EXEC is all ones here: the loop is in uniform control flow.
+        auto hot_load = [&](auto h_tag, int n, char* stage, uint32_t live) {
+            constexpr int H = decltype(h_tag)::value;
+            constexpr int A0 = H == 1 ? Cfg::NCHA / 2 : 0, A1 = H == 0 ? Cfg::NCHA / 2 : Cfg::NCHA;
+            constexpr int B0 = H == 1 ? Cfg::NCHB / 2 : 0;
+            const bool isA = n < A1 - A0;
+            const int i = isA ? A0 + n : B0 + n - (A1 - A0);
+            const uint32_t o = isA ? offA[i] : offB[i];
+            const char* base = isA ? hotA : hotB;
+            const uint32_t dst = lds0 + (uint32_t)(stage - smem) + (uint32_t)((isA ? 0 : BM * ROWB) + i * 4096 + wave_s * 1024);
+            asm volatile(
+                "s_mov_b32 m0, %2\n\t"
+                "s_mov_b32 exec_lo, %3\n\t"
+                "s_mov_b32 exec_hi, %3\n\t"
+                "global_load_lds_dwordx4 %0, %1\n\t"
+                "s_mov_b64 exec, -1"
+                :
+                : "v"(o), "s"(base), "s"(dst), "s"(live)
+                : "memory");
+        };
+        auto wait_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+        // fragment u (A fragments first) of k16 step ks of the tile at `stage` into buffer nb
+        auto read_unit = [&](int ks, int nb, int u, const char* stage) {
+            const int coff = ((2 * ks) ^ fsw) << 4;
+            if (u < TM) {
+                if constexpr (ARC) fa[nb][u] = read_tr(stage + a_rc[u] + 16 * ks * (BM * 2), BM * 2);
+                else fa[nb][u] = *reinterpret_cast<const bf16x8*>(stage + a_off + u * 32 * ROWB + coff);
+            } else {
+                const int j = u - TM;
+                if constexpr (BRC) fb[nb][j] = read_tr(stage + b_rc[j] + 16 * ks * (BN * 2), BN * 2);
+                else fb[nb][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 32 * ROWB + coff);
+            }
+        };
+        // One k16 step with the instruction order fixed by hand (a scheduling fence after every slot): the NM
+        // MFMAs on fragment buffer CB; after MFMA q the fragment reads of slot q (step KS of the tile at
+        // `fstage`, into the other buffer) and, when LD is 0 or 1, the loads of slot q (half LD of the tile at
+        // hotA / hotB into `lstage`).
+        constexpr int NU = TM + TN, UPS = (NU + NM - 1) / NM;  // fragments, fragments per slot
+        auto kstep = [&](auto cb_tag, auto ks_tag, auto ld_tag, const char* fstage, char* lstage, uint32_t live) {
+            constexpr int CB = decltype(cb_tag)::value, KS = decltype(ks_tag)::value, LD = decltype(ld_tag)::value;
+#pragma unroll
+            for (int q = 0; q < NM; ++q) {
+                const int i = q / TN, j = q % TN;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[CB][j], fa[CB][i], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int u = q * UPS; u < (q + 1) * UPS && u < NU; ++u) read_unit(KS, CB ^ 1, u, fstage);
+                if constexpr (LD >= 0) {
+                    if (q >= NM - NSL) {
+#pragma unroll
+                        for (int n = (q - (NM - NSL)) * LPS; n < (q - (NM - NSL) + 1) * LPS; ++n)
+                            hot_load(ld_tag, n, lstage, live);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        using I0 = std::integral_constant<int, 0>;
+        using I1 = std::integral_constant<int, 1>;
+        using I2 = std::integral_constant<int, 2>;
+        using I3 = std::integral_constant<int, 3>;
+        using NOLD = std::integral_constant<int, -1>;
+        if (kt_begin < kt_end) {
+            uint32_t all_lanes;
+            asm("s_mov_b32 %0, -1" : "=s"(all_lanes));
+            hot_setup(kt_begin);
+#pragma unroll
+            for (int n = 0; n < Cfg::NCH; ++n) hot_load(I2{}, n, smem, all_lanes);
+            wait_loads();
+            __syncthreads();
+            load_frags(smem, 0, 0);
+            if (kt_begin + 1 < kt_end) {
+                hot_advance(kt_begin + 1);
+#pragma unroll
+                for (int n = 0; n < NL; ++n) hot_load(I0{}, n, smem + STAGE, all_lanes);
+            }
+        }
+        for (int kt = kt_begin; kt < kt_end; ++kt) {
+            char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
+            char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
+            // all ones while the tile exists: the sign of (tile - kt_end), computed in assembly so that it is
+            // certain to sit in a scalar register (hot_load moves it into EXEC)
+            uint32_t live1, live2;
+            asm("s_sub_i32 %0, %1, %2\n\ts_ashr_i32 %0, %0, 31" : "=s"(live1) : "s"(kt + 1), "s"(kt_end) : "scc");
+            asm("s_sub_i32 %0, %1, %2\n\ts_ashr_i32 %0, %0, 31" : "=s"(live2) : "s"(kt + 2), "s"(kt_end) : "scc");
+            kstep(I0{}, I1{}, I1{}, cur, nxt, live1);  // + second half of tile kt+1
+            if (kt + 2 < kt_end) hot_advance(kt + 2);
+            kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
+            kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
+            wait_loads();
+            __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
+            kstep(I1{}, I0{}, I0{}, nxt, cur, live2);  // + first half of tile kt+2 (harmless stale reads after the last tile)
+        }
     }
     __syncthreads();  // LDS is free for the epilogue
 
@@ -511,9 +692,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     }
 }
 
-template <int BM, int BN, int EPI, bool ARC, bool BRC>
-hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC>;
+template <int BM, int BN, int EPI, bool ARC, bool BRC, bool KTAIL>
+hipError_t launch_nt_k(const GemmParams& p, hipStream_t st) {
+    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, KTAIL>;
     constexpr int smem = NtCfg<BM, BN>::SMEM;
     static bool attr_set = false;
     if (!attr_set) {
@@ -526,6 +707,12 @@ hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
     dim3 grid((tiles + 7) / 8 * 8, EPI == EPI_F32_SPLITK ? p.splits : 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
     return hipGetLastError();
+}
+
+template <int BM, int BN, int EPI, bool ARC, bool BRC>
+hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
+    const bool tail = (p.A[0].K % BK) != 0 || (p.A[1].K % BK) != 0;
+    return tail ? launch_nt_k<BM, BN, EPI, ARC, BRC, true>(p, st) : launch_nt_k<BM, BN, EPI, ARC, BRC, false>(p, st);
 }
 
 }  // namespace
