@@ -41,29 +41,6 @@ constexpr int ROWB = 128;  // bytes of one LDS row (64 bf16)
 #define LOQT_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
 #define LOQT_GLB_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-// interleave the NR fragment reads of the next k16 step one-to-one with the NM MFMAs of this one
-#define LOQT_SCHED_GROUP()                                               \
-    do {                                                                 \
-        _Pragma("unroll") for (int q_ = 0; q_ < NR; ++q_) {              \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           \
-        }                                                                \
-        if (NM > NR) __builtin_amdgcn_sched_group_barrier(0x008, NM - NR, 0); \
-        __builtin_amdgcn_sched_barrier(0);                               \
-    } while (0)
-
-// the same for a k16 step that also carries NL direct loads: reads on the first MFMAs, loads on the last
-// ones (DPS reads on each of the first NRS MFMAs, LPS loads on each of the last NSL)
-#define LOQT_SCHED_GROUP_LD()                                                        \
-    do {                                                                             \
-        _Pragma("unroll") for (int q_ = 0; q_ < NM; ++q_) {                          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       \
-            if (q_ < NRS) __builtin_amdgcn_sched_group_barrier(0x100, DPS, 0);       \
-            if (q_ >= NM - NSL) __builtin_amdgcn_sched_group_barrier(0x020, LPS, 0); \
-        }                                                                            \
-        __builtin_amdgcn_sched_barrier(0);                                           \
-    } while (0)
-
 __device__ __forceinline__ int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
 __device__ __forceinline__ uint32_t nib4(uint32_t word, int e) {
@@ -85,15 +62,13 @@ struct NtCfg {
     static constexpr int SMEM = (SMEM_MAIN > SMEM_EPI ? SMEM_MAIN : SMEM_EPI) + 64;
 };
 
-// KTAIL = false: every K segment is a whole number of k-tiles (the host checks); the main loop then has no
-// branch around its loads and spreads them between the MFMAs.  KTAIL = true: the general loop.
-template <int BM, int BN, int EPI, bool ARC, bool BRC, bool KTAIL>
+template <int BM, int BN, int EPI, bool ARC, bool BRC>
 __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     using Cfg = NtCfg<BM, BN>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE;
-    constexpr int NM = TM * TN, NR = TM * (ARC ? 2 : 1) + TN * (BRC ? 2 : 1);  // MFMAs / LDS reads per k16 step
-    constexpr int NL = Cfg::NCH / 2;                                           // direct loads of half a k-tile
-    constexpr int DPS = (NR + NM - 1) / NM, NRS = (NR + DPS - 1) / DPS, LPS = (NL + NM - 1) / NM, NSL = NL / LPS;
+    constexpr int NM = TM * TN;  // MFMAs per k16 step
+    constexpr int NL = Cfg::NCH / 2;                    // direct loads of half a k-tile
+    constexpr int LPS = (NL + NM - 1) / NM, NSL = NL / LPS;  // LPS loads after each of the last NSL MFMAs of a k16 step
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -147,78 +122,75 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     // Addresses are a wave-uniform 64-bit base (operand pointer + tile origin + K offset, scalar
     // registers) plus a 32-bit per-lane byte offset inside the tile's rows, so the loads use the
     // scalar-base form and no 64-bit address arithmetic runs on the vector unit.
-    auto stage_operand = [&](auto rc_tag, auto br_tag, const Operand& O, int row0, int k0, char* tile) {
+    // A k-tile that is not full (the last one of a K segment whose extent is not a multiple of 64) takes the
+    // path below instead: through registers, elements past K zeroed, ordinary LDS stores.
+    auto tail_operand = [&](auto rc_tag, auto br_tag, const void* optr, int64_t old, int orows, int oK, int row0, int k0,
+                            char* tile) {
         constexpr bool RC = decltype(rc_tag)::value;
         constexpr int BR = decltype(br_tag)::value;
         constexpr int NC = BR / 32;  // chunks per thread
         // a tile that lies wholly past the operand's last row (the merge walks the padding columns of the
         // code matrix, which can exceed `in` by more than a tile) reads the operand's first rows instead:
         // its products are never used, and the clamps below then never go negative
-        if (row0 >= O.rows) row0 = 0;
-        const int kleft = O.K - k0;
-        const uint32_t ld2 = (uint32_t)O.ld * 2u;  // row pitch in bytes (a tile spans < 2^32 bytes)
+        if (row0 >= orows) row0 = 0;
+        const int kleft = oK - k0;
+        const uint32_t ld2 = (uint32_t)old * 2u;  // row pitch in bytes (a tile spans < 2^32 bytes)
         if constexpr (!RC) {
             const int r0 = tid >> 3;
             const int kc = (tid & 7) ^ swz(r0);
-            const int rlast = O.rows - 1 - row0;  // rows past the end: any valid row
-            const char* sbase = reinterpret_cast<const char*>(O.ptr) + ((int64_t)row0 * O.ld + k0) * 2;
-            if (kleft >= BK) {
-#pragma unroll
-                for (int i = 0; i < NC; ++i) {
-                    const uint32_t off = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
-                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(sbase + off),
-                                                     LOQT_LDS_PTR(tile + i * 4096 + wave * 1024), 16, 0, 0);
-                }
-            } else {
-                // K tail: through registers, elements past K zeroed
-                const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
+            const int rlast = orows - 1 - row0;  // rows past the end: any valid row
+            const char* sbase = reinterpret_cast<const char*>(optr) + ((int64_t)row0 * old + k0) * 2;
+            const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
 #pragma unroll 1
-                for (int i = 0; i < NC; ++i) {
-                    const uint32_t off = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (nv > 0) {
-                        v = *reinterpret_cast<const uint4*>(sbase + off);
-                        uint32_t* w = reinterpret_cast<uint32_t*>(&v);
+            for (int i = 0; i < NC; ++i) {
+                const uint32_t off = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (nv > 0) {
+                    v = *reinterpret_cast<const uint4*>(sbase + off);
+                    uint32_t* w = reinterpret_cast<uint32_t*>(&v);
 #pragma unroll
-                        for (int d = 0; d < 4; ++d) {
-                            if (2 * d >= nv) w[d] = 0;
-                            else if (2 * d + 1 >= nv) w[d] &= 0xffffu;
-                        }
+                    for (int d = 0; d < 4; ++d) {
+                        if (2 * d >= nv) w[d] = 0;
+                        else if (2 * d + 1 >= nv) w[d] &= 0xffffu;
                     }
-                    *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
                 }
+                *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
             }
         } else {
             constexpr int CPR = BR / 8;       // chunks per k row
             constexpr int KPI = 256 / CPR;    // k rows covered by one pass of the 256 threads
             const int kq = tid / CPR;         // k of chunk i is i*KPI + kq  (KPI is a multiple of 4)
             const int logical = (tid % CPR) ^ (4 * (kq & 3));
-            const int clast = (((O.rows - 1) >> 3) << 3) - row0;  // columns past the end: any valid chunk
-            const char* sbase = reinterpret_cast<const char*>(O.ptr) + ((int64_t)k0 * O.ld + row0) * 2;
+            const int clast = (((orows - 1) >> 3) << 3) - row0;  // columns past the end: any valid chunk
+            const char* sbase = reinterpret_cast<const char*>(optr) + ((int64_t)k0 * old + row0) * 2;
             const uint32_t off0 = (uint32_t)kq * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
-            if (kleft >= BK) {
-#pragma unroll
-                for (int i = 0; i < NC; ++i)
-                    __builtin_amdgcn_global_load_lds(LOQT_GLB_PTR(sbase + (off0 + (uint32_t)(i * KPI) * ld2)),
-                                                     LOQT_LDS_PTR(tile + i * 4096 + wave * 1024), 16, 0, 0);
-            } else {
 #pragma unroll 1
-                for (int i = 0; i < NC; ++i) {
-                    uint4 v = make_uint4(0, 0, 0, 0);
-                    if (i * KPI + kq < kleft)
-                        v = *reinterpret_cast<const uint4*>(sbase + (off0 + (uint32_t)(i * KPI) * ld2));
-                    *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
-                }
+            for (int i = 0; i < NC; ++i) {
+                uint4 v = make_uint4(0, 0, 0, 0);
+                if (i * KPI + kq < kleft) v = *reinterpret_cast<const uint4*>(sbase + (off0 + (uint32_t)(i * KPI) * ld2));
+                *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
             }
         }
     };
-    auto stage_tile = [&](int kt, char* stage) {
-        const int seg = kt >= nkt0 ? 1 : 0;
+    // the operand of K segment `seg`, field by field (selects on scalars: a run-time index into the by-value
+    // parameter block, or a copy of an Operand, would go through scratch memory)
+    auto a_ptr = [&](bool seg) { return seg ? p.A[1].ptr : p.A[0].ptr; };
+    auto a_ld = [&](bool seg) { return seg ? p.A[1].ld : p.A[0].ld; };
+    auto a_rows = [&](bool seg) { return seg ? p.A[1].rows : p.A[0].rows; };
+    auto b_ptr = [&](bool seg) { return part1 ? p.Bx.ptr : (seg ? p.B[1].ptr : p.B[0].ptr); };
+    auto b_ld = [&](bool seg) { return part1 ? p.Bx.ld : (seg ? p.B[1].ld : p.B[0].ld); };
+    auto b_rows = [&](bool seg) { return part1 ? p.Bx.rows : (seg ? p.B[1].rows : p.B[0].rows); };
+    auto tail_tile = [&](int kt, char* stage) {
+        const bool seg = kt >= nkt0;
         const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
-        stage_operand(std::integral_constant<bool, ARC>{}, std::integral_constant<int, BM>{}, p.A[seg], m0, k0, stage);
-        stage_operand(std::integral_constant<bool, BRC>{}, std::integral_constant<int, BN>{},
-                      part1 ? p.Bx : p.B[seg], n0, k0, stage + BM * ROWB);
+        const int segK = seg ? p.A[1].K : p.A[0].K;
+        tail_operand(std::integral_constant<bool, ARC>{}, std::integral_constant<int, BM>{}, a_ptr(seg), a_ld(seg), a_rows(seg),
+                     segK, m0, k0, stage);
+        tail_operand(std::integral_constant<bool, BRC>{}, std::integral_constant<int, BN>{}, b_ptr(seg), b_ld(seg), b_rows(seg),
+                     segK, n0, k0, stage + BM * ROWB);
     };
+    // index of the tail tile of each segment, or -1
+    const int tail0 = (p.A[0].K % BK) ? nkt0 - 1 : -1, tail1 = (p.A[1].K % BK) ? nkt0 + nkt1 - 1 : -1;
 
     // ---- fragments.  A lane holds row (lane & 31) of a 32-row fragment and the 8 k-values
     // 16*ks + 8*(lane >> 5) .. +7.  K-contiguous tiles: one 16-byte read of logical chunk 2*ks + (lane>>5).
@@ -267,43 +239,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             else fb[buf][j] = *reinterpret_cast<const bf16x8*>(stage + b_off + j * 32 * ROWB + coff);
         }
     };
-    // transposed accumulation: D^T = B_frag A_frag^T, so lane = m, registers = n
-    auto mfmas = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][j], fa[buf][i], acc[i][j], 0, 0, 0);
-    };
-
-    if constexpr (KTAIL) {
-        if (kt_begin < kt_end) {
-            stage_tile(kt_begin, smem);
-            __syncthreads();  // waits for the direct loads (vmcnt) and the tail writes (lgkmcnt)
-            load_frags(smem, 0, 0);
-            if (kt_begin + 1 < kt_end) stage_tile(kt_begin + 1, smem + STAGE);
-        }
-        for (int kt = kt_begin; kt < kt_end; ++kt) {
-            char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
-            char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
-            load_frags(cur, 1, 1);
-            mfmas(0);
-            LOQT_SCHED_GROUP();
-            load_frags(cur, 2, 0);
-            mfmas(1);
-            LOQT_SCHED_GROUP();
-            load_frags(cur, 3, 1);
-            mfmas(0);
-            LOQT_SCHED_GROUP();
-            __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
-            load_frags(nxt, 0, 0);   // (harmless stale read after the last tile)
-            if (kt + 2 < kt_end) stage_tile(kt + 2, cur);
-            mfmas(1);
-            LOQT_SCHED_GROUP();
-        }
-    } else {
-        // Whole k-tiles only.  The lane offsets of a thread's chunks are loop-invariant registers (per K segment)
-        // and the tile origin is a scalar pointer that advances by a constant, so a load is one instruction plus
+    {
+        // ---- main loop.  The lane offsets of a thread's chunks are loop-invariant registers (per K segment) and
+        // the tile origin is a scalar pointer that advances by a constant, so a load is one instruction plus
         // scalar bookkeeping and can sit between the MFMAs.  A k-tile is issued in two halves: the first during
         // the last k16 step of the tile two before it (right after the barrier that frees its stage), the second
         // during the first k16 step of the tile before it; the two k16 steps in between carry no loads, so
@@ -316,7 +254,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             constexpr bool RC = decltype(rc_tag)::value;
             constexpr int BR = decltype(br_tag)::value;
             constexpr int NC = BR / 32;
-            if (row0 >= orows) row0 = 0;  // as in stage_operand
+            if (row0 >= orows) row0 = 0;  // as in tail_operand
             const uint32_t ld2 = (uint32_t)old * 2u;
             if constexpr (!RC) {
                 const int r0 = tid >> 3;
@@ -342,18 +280,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         auto hot_setup = [&](int kt) {  // kt: a tile of the range
             const bool seg = kt >= nkt0;
             const int k0 = (kt - (seg ? nkt0 : 0)) * BK;
-            // field-by-field selects keep everything in scalar registers (a run-time index into the by-value
-            // parameter block, or a copy of an Operand, would go through scratch memory)
-            const void* aptr = seg ? p.A[1].ptr : p.A[0].ptr;
-            const int64_t ald = seg ? p.A[1].ld : p.A[0].ld;
-            const int arows = seg ? p.A[1].rows : p.A[0].rows;
-            const void* bptr = part1 ? p.Bx.ptr : (seg ? p.B[1].ptr : p.B[0].ptr);
-            const int64_t bld = part1 ? p.Bx.ld : (seg ? p.B[1].ld : p.B[0].ld);
-            const int brows = part1 ? p.Bx.rows : (seg ? p.B[1].rows : p.B[0].rows);
-            hot_operand(std::integral_constant<bool, ARC>{}, std::integral_constant<int, BM>{}, aptr, ald, arows, m0, k0, offA,
-                        hotA, stepA);
-            hot_operand(std::integral_constant<bool, BRC>{}, std::integral_constant<int, BN>{}, bptr, bld, brows, n0, k0, offB,
-                        hotB, stepB);
+            hot_operand(std::integral_constant<bool, ARC>{}, std::integral_constant<int, BM>{}, a_ptr(seg), a_ld(seg),
+                        a_rows(seg), m0, k0, offA, hotA, stepA);
+            hot_operand(std::integral_constant<bool, BRC>{}, std::integral_constant<int, BN>{}, b_ptr(seg), b_ld(seg),
+                        b_rows(seg), n0, k0, offB, hotB, stepB);
         };
         auto hot_advance = [&](int kt) {  // move on to tile kt, the successor of the current one (kt < kt_end)
             if (kt == nkt0) hot_setup(kt);
@@ -427,36 +357,61 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         using I2 = std::integral_constant<int, 2>;
         using I3 = std::integral_constant<int, 3>;
         using NOLD = std::integral_constant<int, -1>;
+        // all ones when tile t exists and is a full tile (its direct loads are live), else zero; computed in
+        // assembly so that it is certain to sit in a scalar register (hot_load moves it into EXEC)
+        auto live_mask = [&](int t) {
+            uint32_t m;
+            asm("s_sub_i32 %0, %1, %2\n\t"
+                "s_ashr_i32 %0, %0, 31\n\t"
+                "s_cmp_lg_u32 %1, %3\n\t"
+                "s_cselect_b32 %0, %0, 0\n\t"
+                "s_cmp_lg_u32 %1, %4\n\t"
+                "s_cselect_b32 %0, %0, 0"
+                : "=&s"(m)
+                : "s"(t), "s"(kt_end), "s"(tail0), "s"(tail1)
+                : "scc");
+            return m;
+        };
+        auto is_tail = [&](int t) { return t == tail0 || t == tail1; };
         if (kt_begin < kt_end) {
-            uint32_t all_lanes;
-            asm("s_mov_b32 %0, -1" : "=s"(all_lanes));
             hot_setup(kt_begin);
+            if (is_tail(kt_begin)) {
+                tail_tile(kt_begin, smem);
+            } else {
+                const uint32_t live = live_mask(kt_begin);
 #pragma unroll
-            for (int n = 0; n < Cfg::NCH; ++n) hot_load(I2{}, n, smem, all_lanes);
+                for (int n = 0; n < Cfg::NCH; ++n) hot_load(I2{}, n, smem, live);
+            }
             wait_loads();
             __syncthreads();
             load_frags(smem, 0, 0);
             if (kt_begin + 1 < kt_end) {
                 hot_advance(kt_begin + 1);
+                if (is_tail(kt_begin + 1)) {
+                    tail_tile(kt_begin + 1, smem + STAGE);
+                } else {
+                    const uint32_t live = live_mask(kt_begin + 1);
 #pragma unroll
-                for (int n = 0; n < NL; ++n) hot_load(I0{}, n, smem + STAGE, all_lanes);
+                    for (int n = 0; n < NL; ++n) hot_load(I0{}, n, smem + STAGE, live);
+                }
             }
         }
+        uint32_t live1 = live_mask(kt_begin + 1);  // tile kt+1 at the top of iteration kt
         for (int kt = kt_begin; kt < kt_end; ++kt) {
             char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
             char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
-            // all ones while the tile exists: the sign of (tile - kt_end), computed in assembly so that it is
-            // certain to sit in a scalar register (hot_load moves it into EXEC)
-            uint32_t live1, live2;
-            asm("s_sub_i32 %0, %1, %2\n\ts_ashr_i32 %0, %0, 31" : "=s"(live1) : "s"(kt + 1), "s"(kt_end) : "scc");
-            asm("s_sub_i32 %0, %1, %2\n\ts_ashr_i32 %0, %0, 31" : "=s"(live2) : "s"(kt + 2), "s"(kt_end) : "scc");
+            const uint32_t live2 = live_mask(kt + 2);
             kstep(I0{}, I1{}, I1{}, cur, nxt, live1);  // + second half of tile kt+1
             if (kt + 2 < kt_end) hot_advance(kt + 2);
             kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
             kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
             wait_loads();
             __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
+            if (live2 == 0) {        // no tile kt+2, or a tail tile (rare)
+                if (kt + 2 < kt_end) tail_tile(kt + 2, cur);
+            }
             kstep(I1{}, I0{}, I0{}, nxt, cur, live2);  // + first half of tile kt+2 (harmless stale reads after the last tile)
+            live1 = live2;
         }
     }
     __syncthreads();  // LDS is free for the epilogue
@@ -692,9 +647,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     }
 }
 
-template <int BM, int BN, int EPI, bool ARC, bool BRC, bool KTAIL>
-hipError_t launch_nt_k(const GemmParams& p, hipStream_t st) {
-    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, KTAIL>;
+template <int BM, int BN, int EPI, bool ARC, bool BRC>
+hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
+    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC>;
     constexpr int smem = NtCfg<BM, BN>::SMEM;
     static bool attr_set = false;
     if (!attr_set) {
@@ -707,12 +662,6 @@ hipError_t launch_nt_k(const GemmParams& p, hipStream_t st) {
     dim3 grid((tiles + 7) / 8 * 8, EPI == EPI_F32_SPLITK ? p.splits : 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
     return hipGetLastError();
-}
-
-template <int BM, int BN, int EPI, bool ARC, bool BRC>
-hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    const bool tail = (p.A[0].K % BK) != 0 || (p.A[1].K % BK) != 0;
-    return tail ? launch_nt_k<BM, BN, EPI, ARC, BRC, true>(p, st) : launch_nt_k<BM, BN, EPI, ARC, BRC, false>(p, st);
 }
 
 }  // namespace
