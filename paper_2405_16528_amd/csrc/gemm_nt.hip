@@ -111,6 +111,32 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // merge with 128x128 tiles: the old codes and scales of this lane's 64-blocks are fetched here, ahead of the
+    // product, so that the epilogue does not start with a round trip to memory (18 registers; the 256-wide tiles
+    // have none to spare).  Row m = m0 + wm*WTM + ti*32 + (lane & 31), block b of the wave's columns.
+    constexpr bool MERGE_PREFETCH = EPI == EPI_MERGE && BM == 128 && BN == 128;
+    constexpr int NPB = MERGE_PREFETCH ? TM * (TN / 2) : 1;
+    uint4 pre_cw[NPB][2];
+    float pre_am[NPB];
+    if constexpr (MERGE_PREFETCH) {
+        const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
+#pragma unroll
+        for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+            for (int b = 0; b < TN / 2; ++b) {
+                const int m = m0 + wm * Cfg::WTM + ti * 32 + (lane & 31);
+                const int nb = n0 + wn * Cfg::WTN + b * 64;
+                const int k = ti * (TN / 2) + b;
+                pre_cw[k][0] = pre_cw[k][1] = make_uint4(0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u);
+                pre_am[k] = 0.f;
+                if (m < p.M && nb < p.w_ld) {
+                    pre_am[k] = p.w_absmax[m * lda + (nb >> 6)];
+                    pre_cw[k][0] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1));
+                    pre_cw[k][1] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1) + 16);
+                }
+            }
+    }
+
     // ---- staging.  Chunk i of this thread is LDS slot (i*256 + tid) of the operand tile (the LDS side
     // of a direct load is lane-linear); which 16 bytes of global memory go there carries the swizzle.
     //  K-contiguous operand (rows x K): tile [row][64 k], slot -> row slot>>3, physical chunk slot&7,
@@ -565,14 +591,20 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 float wsrc[EPI == EPI_COMP ? 32 : 1];
                 if constexpr (EPI == EPI_MERGE) {
                     float am_old = 0.f;
-                    if (live) am_old = p.w_absmax[m * lda + (nb >> 6)];
                     // the 2 x 16 code bytes of the block (columns nb..nb+63 of row m); both lanes of a pair
                     // load them, this lane owns the half-words (lane >> 5) of each dword
                     uint4 cw4[2];
-                    cw4[0] = cw4[1] = make_uint4(0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u);
-                    if (live) {
-                        cw4[0] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1));
-                        cw4[1] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1) + 16);
+                    if constexpr (MERGE_PREFETCH) {
+                        am_old = pre_am[ti * (TN / 2) + b];
+                        cw4[0] = pre_cw[ti * (TN / 2) + b][0];
+                        cw4[1] = pre_cw[ti * (TN / 2) + b][1];
+                    } else {
+                        if (live) am_old = p.w_absmax[m * lda + (nb >> 6)];
+                        cw4[0] = cw4[1] = make_uint4(0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u);
+                        if (live) {
+                            cw4[0] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1));
+                            cw4[1] = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nb >> 1) + 16);
+                        }
                     }
 #pragma unroll
                     for (int q = 0; q < 8; ++q) {  // q = 4*tt + g: tile tt of the pair, column group g
