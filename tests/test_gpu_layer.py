@@ -40,6 +40,8 @@ SHAPES = [
     (130, 300, 1000, 64),      # K tail not a multiple of 8... (1000 % 64 = 40)
     (515, 1100, 333, 192),     # odd in: pitch padded to 336, K tail 13
     (1000, 5461 // 4, 768, 256),
+    (70, 130, 40, 32),         # every contraction shorter than one k-tile (one tail tile per K segment)
+    (200, 192, 128, 40),       # whole k-tiles in the first K segment, a lone tail tile in the second
 ]
 
 
