@@ -116,7 +116,8 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
  *   FWD_RIGHT, BWD_RIGHT, MERGE_RIGHT: the right-side variant below, with r = columns of Q_q:
  *          bf16 deq(Q_q); forward and backward + the folded weight (out x in bf16); backward +
  *          V = s x deq(Q_q) (T x r bf16) and fp32 slices of dBp
- *   FWD_NQ, BWD_NQ: the unquantised variant below: U resp. Z (T x r bf16) and the fp32 slices of dB
+ *   FWD_NQ, BWD_NQ: the unquantised variant below: U resp. Z (T x r bf16), the fp32 slices of dB and
+ *          the folded weight (out x in bf16)
  */
 size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t r);
 
@@ -270,8 +271,11 @@ loqt_status loqt_init_compensate(const float *W, int64_t ld_w, const float *P, i
  *   loqt_linear_fwd_nq   y  = x W^T + s (x B^T) P^T
  *   loqt_linear_bwd_nq   dx = dy W + s (dy P) B  (dx may be NULL),  dB = s P^T dy^T x  (as loqt_linear_bwd)
  *   loqt_merge_nq        W <- bf16( fp32(W) + s * P B ), in place, round to nearest even (Alg. 1 line 5)
- * Nothing is dequantised, so the rank-r term is carried as a second K segment of the products
- * ([x | U] [W | P]^T and [dy | Z] [W ; B]) and no pass over the weights precedes them.
+ * Nothing is dequantised.  With few tokens the rank-r term is carried as a second K segment of the
+ * products ([x | U] [W | P]^T and [dy | Z] [W ; B]) and no pass over the weights precedes them; from
+ * T (in + out) >= out * in on (or under LOQT_PATH_FOLDED) it is folded into a transient copy of the
+ * weight in the workspace, W_eff = bf16(W + s P B), as in the quantised layer, and y = x W_eff^T,
+ * dx = dy W_eff are single products.
  */
 loqt_status loqt_linear_fwd_nq(const loqt_bf16 *x, int64_t ld_x, int64_t T,
                                const loqt_bf16 *W, int64_t ld_W, const loqt_bf16 *P, int64_t ld_P,

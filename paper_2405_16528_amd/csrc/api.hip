@@ -409,11 +409,13 @@ size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t 
             if (T <= 0) return 0;
             return RightWs(op, T, out, in, r).total;
         case LOQT_OP_MERGE_RIGHT: return RightWs(op, 0, out, in, r).total;
-        case LOQT_OP_FWD_NQ: return T <= 0 ? 0 : bf16_bytes(T, r);
+        // LoQT-nq: U or Z (T x r) first, then the dB slices (backward), then room for the folded weight
+        // W_eff (out x in, bf16), whether or not the path option makes this call fold
+        case LOQT_OP_FWD_NQ: return T <= 0 ? 0 : bf16_bytes(T, r) + bf16_bytes(out, in);
         case LOQT_OP_BWD_NQ: {
             if (T <= 0) return 0;
             const BwdWs L(T, out, in, r);
-            return bf16_bytes(T, r) + (L.total - L.partials);
+            return bf16_bytes(T, r) + (L.total - L.partials) + bf16_bytes(out, in);
         }
         default: return 0;
     }
@@ -994,6 +996,25 @@ loqt_status check_layer_nq(const loqt_bf16* W, int64_t ld_W, const loqt_bf16* P,
 }
 }  // namespace
 
+// W_eff = bf16(W + s P B) for the unquantised layer (the product of loqt_merge_nq, written to `We`, pitch ld_we,
+// instead of over W)
+static hipError_t fold_nq(const loqt_bf16* W, int64_t ld_W, const loqt_bf16* P, int64_t ld_P, const loqt_bf16* B,
+                          int64_t ld_B, int64_t out, int64_t in, int64_t r, float s, uint16_t* We, int64_t ld_we,
+                          hipStream_t st) {
+    GemmParams p;
+    memset(&p, 0, sizeof(p));
+    p.A[0] = bf16_operand(P, ld_P, (int)out, (int)r);
+    p.B[0] = bf16_operand(B, ld_B, (int)in, (int)r);  // r x in: K x rows
+    p.M = (int)out;
+    p.N = (int)in;
+    p.alpha = s;
+    p.C = We;
+    p.ldc = ld_we;
+    p.w_bf16 = W;
+    p.w_bf16_ld = ld_W;
+    return launch_gemm_nt(SLOT_FOLD, EPI_ACC_BF16, false, true, p, st);
+}
+
 loqt_status loqt_linear_fwd_nq(const loqt_bf16* x, int64_t ld_x, int64_t T, const loqt_bf16* W, int64_t ld_W,
                                const loqt_bf16* P, int64_t ld_P, const loqt_bf16* B, int64_t ld_B, int64_t out,
                                int64_t in, int64_t r, float s, loqt_bf16* y, int64_t ld_y, void* ws,
@@ -1001,11 +1022,27 @@ loqt_status loqt_linear_fwd_nq(const loqt_bf16* x, int64_t ld_x, int64_t T, cons
     LOQT_TRY(check_layer_nq(W, ld_W, P, ld_P, B, ld_B, out, in, r));
     LOQT_TRY(check_bf16(x, T, in, ld_x));
     LOQT_TRY(check_bf16(y, T, out, ld_y));
-    LOQT_TRY(check_ws(ws, ws_bytes, bf16_bytes(T, r)));
+    const bool folded = use_folded(T, out, in);
+    LOQT_TRY(check_ws(ws, ws_bytes, bf16_bytes(T, r) + (folded ? bf16_bytes(out, in) : 0)));
     hipStream_t st = (hipStream_t)hip_stream;
     uint16_t* U = reinterpret_cast<uint16_t*>(ws);
     const int64_t ld_u = (int64_t)round_up(r, 8);
     GemmParams p;
+    if (folded) {  // y = x W_eff^T with the rank-r term folded into a transient copy of the weight
+        uint16_t* We = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(ws) + bf16_bytes(T, r));
+        const int64_t ld_we = (int64_t)round_up(in, 8);
+        LOQT_HIP(fold_nq(W, ld_W, P, ld_P, B, ld_B, out, in, r, s, We, ld_we, st));
+        memset(&p, 0, sizeof(p));
+        p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
+        p.B[0] = bf16_operand(We, ld_we, (int)out, (int)in);
+        p.M = (int)T;
+        p.N = (int)out;
+        p.alpha = 1.0f;
+        p.C = y;
+        p.ldc = ld_y;
+        LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, false, false, p, st));
+        return LOQT_OK;
+    }
     memset(&p, 0, sizeof(p));  // U = s x B^T
     p.A[0] = bf16_operand(x, ld_x, (int)T, (int)in);
     p.B[0] = bf16_operand(B, ld_B, (int)r, (int)in);
@@ -1044,10 +1081,14 @@ loqt_status loqt_linear_bwd_nq(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf
     if (!aligned(dB, dB_dtype == LOQT_BF16 ? 2 : 4)) return LOQT_MISALIGNED;
     const BwdWs L(T, out, in, r);  // only its split choice and slice pitch are used here
     const size_t z_bytes = bf16_bytes(T, r);
-    LOQT_TRY(check_ws(ws, ws_bytes, z_bytes + (L.total - L.partials)));
+    const bool folded = dx && use_folded(T, out, in);
+    LOQT_TRY(check_ws(ws, ws_bytes, z_bytes + (L.total - L.partials) + (folded ? bf16_bytes(out, in) : 0)));
     hipStream_t st = (hipStream_t)hip_stream;
     uint16_t* Z = reinterpret_cast<uint16_t*>(ws);
     float* part = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + z_bytes);
+    uint16_t* We = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(ws) + z_bytes + (L.total - L.partials));
+    const int64_t ld_we = (int64_t)round_up(in, 8);
+    if (folded) LOQT_HIP(fold_nq(W, ld_W, P, ld_P, B, ld_B, out, in, r, s, We, ld_we, st));
     const int64_t ld_z = (int64_t)round_up(r, 8);
     GemmParams p;
     memset(&p, 0, sizeof(p));  // Z = s dy P: P is out x r, i.e. K x rows
@@ -1059,12 +1100,14 @@ loqt_status loqt_linear_bwd_nq(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf
     p.C = Z;
     p.ldc = ld_z;
     LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, false, true, p, st));
-    if (dx) {  // dx = [dy | Z] [W ; B]: W is out x in and B is r x in, both K x rows
+    if (dx) {  // dx = [dy | Z] [W ; B]: W is out x in and B is r x in, both K x rows; folded: dx = dy W_eff
         memset(&p, 0, sizeof(p));
         p.A[0] = bf16_operand(dy, ld_dy, (int)T, (int)out);
-        p.B[0] = bf16_operand(W, ld_W, (int)in, (int)out);
-        p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
-        p.B[1] = bf16_operand(B, ld_B, (int)in, (int)r);
+        p.B[0] = folded ? bf16_operand(We, ld_we, (int)in, (int)out) : bf16_operand(W, ld_W, (int)in, (int)out);
+        if (!folded) {
+            p.A[1] = bf16_operand(Z, ld_z, (int)T, (int)r);
+            p.B[1] = bf16_operand(B, ld_B, (int)in, (int)r);
+        }
         p.M = (int)T;
         p.N = (int)in;
         p.alpha = 1.0f;

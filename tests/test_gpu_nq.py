@@ -11,6 +11,16 @@ pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
+@pytest.fixture(params=["auto", "factored", "folded"], autouse=True)
+def path(request):
+    """Every test runs under each form of the rank-r term: carried as a second K segment, folded into a
+    transient copy of the weight, or chosen by the token count."""
+    from paper_2405_16528_amd import binding as L
+    L.set_path({"auto": L.PATH_AUTO, "factored": L.PATH_PREPASS, "folded": L.PATH_FOLDED}[request.param])
+    yield request.param
+    L.set_path(L.PATH_AUTO)
+
+
 def _setup(T, out, inp, r, seed, sigma_B=2e-2):
     from tests import gpu_util as G
     rng = synth.rng_for(seed, "nq-gpu", str(T), str(out), str(inp), str(r))
