@@ -31,6 +31,15 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
   step   (Alg. 1 line 9: B_{t+1} = B_t - rho(G^B_t), rho = Adam; sec. 2.5 last paragraph and
           the hyper-parameter appendix: W is updated at steps T_i whose gaps are tau + psi^i).
 
+  dq     (sec. 2.4: "the quantization state itself is re-quantized ... following [QLoRA]"): the fp32
+          block scales of an NF4 matrix are themselves stored in 8 bits.  PARITY UNPINNED BY THE PAPER:
+          it gives no format.  Reading taken (the cited method's own description: the scales, being
+          positive, have their mean subtracted and are quantised to 8-bit floats in blocks of 256 with one
+          fp32 constant per block): d = fl32(M - mean); c1 = max |d| over 256 consecutive scales;
+          code = E4M3( fl32( fl32(d / c1) * 448 ) ), E4M3 the 8-bit float with 4 exponent and 3 mantissa
+          bits, bias 7, no infinities, largest value 448, round to nearest even, saturating;
+          M' = fl32( fl32( fl32(E4M3^-1(code) * c1) / 448 ) + mean ).
+
 Layout convention used by every function here ("logical" form, no padding):
   codes  : uint8 array (rows, cols), one code 0..15 per element
   absmax : float32 array (rows, ceil(cols/64)); blocks run along a row and never
@@ -347,3 +356,78 @@ def loqt_merge_dense_f32(Wq, Pq, B, s):
     """Alg. 1 line 5 as printed: W <- W_Q + s P_Q B, kept in full precision (fp32 of the fp64 sum);
     the input of Alg. 2's Initialize."""
     return loqt_merge_f64(Wq, Pq, B, s).astype(np.float32)
+
+
+# ---------------------------------------------------------------------------------------------
+# double quantisation of the block scales (sec. 2.4; format: see the header, parity unpinned)
+# ---------------------------------------------------------------------------------------------
+E4M3_MAX = 448.0
+DQ_BLOCK = 256
+
+
+def e4m3_decode(code: np.ndarray) -> np.ndarray:
+    """8-bit float, 1 sign / 4 exponent / 3 mantissa bits, bias 7, no infinities -> float32 (exact).
+    Exponent field 0 holds the subnormals m * 2^-9; code 0x7f / 0xff is the NaN of the format."""
+    code = np.asarray(code, dtype=np.uint8).astype(np.int64)
+    sign = np.where(code & 0x80, -1.0, 1.0)
+    e = (code >> 3) & 0xF
+    m = code & 0x7
+    mag = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * 2.0 ** (e.astype(np.float64) - 7))
+    out = sign * mag
+    out = np.where((e == 15) & (m == 7), np.nan, out)
+    return out.astype(np.float32)
+
+
+def e4m3_encode(x: np.ndarray) -> np.ndarray:
+    """float32 -> nearest representable E4M3 value, ties to the even mantissa, saturating at +-448.
+    Plain definition: among the 253 finite codes pick the one whose value is nearest; on a tie the code
+    with the even mantissa bit pattern; the sign bit follows the sign of x (so -0.0 -> 0x80)."""
+    x = np.asarray(x, dtype=np.float32)
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], dtype=np.uint8)
+    pos = codes[codes < 0x80]
+    vals = e4m3_decode(pos).astype(np.float64)  # ascending with the code
+    a = np.minimum(np.abs(x.astype(np.float64)), E4M3_MAX)
+    hi = np.searchsorted(vals, a, side="left")          # first value >= a
+    hi = np.minimum(hi, len(vals) - 1)
+    lo = np.maximum(hi - 1, 0)
+    dlo, dhi = a - vals[lo], vals[hi] - a
+    pick_hi = (dhi < dlo) | ((dhi == dlo) & ((pos[hi] & 1) == 0))
+    mag = np.where(pick_hi, pos[hi], pos[lo]).astype(np.uint8)
+    mag = np.where(a == vals[hi], pos[hi], mag).astype(np.uint8)
+    sign = (np.signbit(x)).astype(np.uint8) << 7
+    return (mag | sign).astype(np.uint8)
+
+
+def absmax_dq_compress(absmax: np.ndarray, mean=None):
+    """Block scales (any shape, taken flat, fp32) -> (codes uint8 [n], c1 float32 [ceil(n/256)], mean float32).
+    `mean` may be supplied (the format stores it, so any fp32 next to the true mean is a valid choice);
+    by default it is the fp64 mean rounded to fp32."""
+    a = np.asarray(absmax, dtype=np.float32).reshape(-1)
+    n = a.size
+    if mean is None:
+        mean = np.float32(a.astype(np.float64).sum() / max(n, 1))
+    mean = np.float32(mean)
+    d = (a - mean).astype(np.float32)
+    nb = (n + DQ_BLOCK - 1) // DQ_BLOCK
+    c1 = np.zeros(nb, dtype=np.float32)
+    codes = np.zeros(n, dtype=np.uint8)
+    for b in range(nb):
+        blk = d[b * DQ_BLOCK:(b + 1) * DQ_BLOCK]
+        c = np.float32(np.max(np.abs(blk)))
+        c1[b] = c
+        if c > 0:
+            t = (blk / c).astype(np.float32)
+            u = (t * np.float32(E4M3_MAX)).astype(np.float32)
+            codes[b * DQ_BLOCK:b * DQ_BLOCK + blk.size] = e4m3_encode(u)
+        else:
+            codes[b * DQ_BLOCK:b * DQ_BLOCK + blk.size] = e4m3_encode(blk)  # +-0
+    return codes, c1, mean
+
+
+def absmax_dq_expand(codes: np.ndarray, c1: np.ndarray, mean) -> np.ndarray:
+    codes = np.asarray(codes, dtype=np.uint8).reshape(-1)
+    v = e4m3_decode(codes)
+    cc = np.repeat(np.asarray(c1, dtype=np.float32), DQ_BLOCK)[:codes.size]
+    t = (v * cc).astype(np.float32)
+    t = (t / np.float32(E4M3_MAX)).astype(np.float32)
+    return (t + np.float32(mean)).astype(np.float32)
