@@ -105,7 +105,7 @@ def extras(L, synth, torch, wl, full_precision, layers):
 
     gen = torch.Generator(device=dev)
     gen.manual_seed(1)
-    res = {"codec": [], "merge_small_rank": [], "init_compensate": []}
+    res = {"codec": [], "absmax_dq": [], "merge_small_rank": [], "init_compensate": []}
     for (out, inp), (Wd, Pd) in full_precision.items():
         n = out * inp
         Wq = L.nf4_quantize(Wd)
@@ -117,6 +117,18 @@ def extras(L, synth, torch, wl, full_precision, layers):
                              "dequantize_bf16_us": t_d, "dequantize_bf16_GBs": n * 2.5625 / t_d / 1e3,
                              "dequantize_frac_hbm": n * 2.5625 / t_d / 1e3 / PEAK_HBM_GBS})
         del Wb
+        # double-quantised block scales (sec. 2.4): three launches over n / 64 scales (launch-sized), the storage
+        # they buy, and what the 8-bit scales do to the dequantised weight
+        a = Wq.absmax.reshape(-1)
+        dq = L.loqt_absmax_dq_compress(a)
+        a2 = L.loqt_absmax_dq_expand(*dq)
+        t_c = timed_us(lambda: L.loqt_absmax_dq_compress(a))
+        t_e = timed_us(lambda: L.loqt_absmax_dq_expand(*dq, out=a2))
+        res["absmax_dq"].append({"shape": f"{out}x{inp}", "scales": a.numel(), "compress_us": t_c, "expand_us": t_e,
+                                 "bytes_per_weight": 0.5 + (a.numel() + 4 * dq[1].numel() + 4) / n,
+                                 "bytes_per_weight_fp32_scales": 0.5 + 4 * a.numel() / n,
+                                 "rms_rel_change_of_scales": float(((a2 - a).double().pow(2).mean().sqrt()
+                                                                   / a.double().pow(2).mean().sqrt()).item())})
         Wq_out = L.NF4Tensor.empty(out, inp)
         for r in (64, 128):
             Pq = L.nf4_quantize(Pd[:, :r].contiguous())

@@ -304,6 +304,33 @@ loqt_status loqt_merge_dense(const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq, con
                              void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * loqt_absmax_dq_compress / loqt_absmax_dq_expand -- double quantisation of the block scales (sec. 2.4:
+ * "the quantization state itself is re-quantized for further efficiency", following the NF4 paper).
+ * The paper gives no format; the one implemented is the cited method's description: the scales, being
+ * positive, have their mean subtracted and are stored as 8-bit floats in blocks of 256 with one fp32
+ * constant per block.  With M[0..n) the fp32 scales of an NF4 matrix taken as a flat array (absmax with
+ * its padding, rows * ld / 64 values):
+ *     mean = fl32( sum M / n )                         (fp64 sum in a fixed order)
+ *     d_j  = fl32(M_j - mean);   c1_b = max |d_j| over block b = 256 consecutive scales
+ *     code_j = E4M3( fl32( fl32(d_j / c1_b) * 448 ) )  (+-0 when c1_b = 0)
+ *     M'_j = fl32( fl32( fl32(E4M3^-1(code_j) * c1_b) / 448 ) + mean )
+ * E4M3: 1 sign, 4 exponent, 3 mantissa bits, bias 7, no infinities, largest value 448, subnormals
+ * m * 2^-9; round to nearest, ties to the even code.  Storage: 8 bits per scale + 32 bits per 256
+ * scales + 32 bits, i.e. 0.5 + 1/64 + 1/4096 bytes per weight instead of 0.5 + 1/16.  The layer calls
+ * take fp32 scales: expand before use, compress what a merge wrote.  |M' - M| <= c1_b / 28 (half a step
+ * at the top of the range) and about |M - mean| / 16 in general, so the weights change: this is a lossy
+ * storage option, not part of the bit-exact codec contract.
+ *   absmax, absmax_out : n fp32 scales (device);  codes8 : n bytes;  c1 : ceil(n / 256) floats;
+ *   mean : one float (device), written by compress, read by expand
+ *   ws   : loqt_absmax_dq_workspace_bytes(n) bytes of scratch, 8-byte aligned (compress only)
+ */
+size_t loqt_absmax_dq_workspace_bytes(int64_t n);
+loqt_status loqt_absmax_dq_compress(const float *absmax, int64_t n, uint8_t *codes8, float *c1, float *mean,
+                                    void *ws, size_t ws_bytes, void *hip_stream);
+loqt_status loqt_absmax_dq_expand(const uint8_t *codes8, const float *c1, const float *mean, int64_t n,
+                                  float *absmax_out, void *hip_stream);
+
+/*
  * loqt_adam_step -- the update between merges (Alg. 1 line 9: B_{t+1} = B_t - rho(G^B_t), rho = Adam;
  * the paper names the optimiser only, so this is the published algorithm with bias correction and no
  * weight decay):

@@ -94,6 +94,12 @@ lib.loqt_merge_schedule.argtypes = [C.c_double, C.c_double, _i64, _i, _P(_i64)]
 lib.loqt_init_compensate.restype = _i
 lib.loqt_init_compensate.argtypes = [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _f, _i, _i, _vp, _vp, _i64, _vp, _i64,
                                      _vp, _sz, _vp]
+lib.loqt_absmax_dq_workspace_bytes.restype = _sz
+lib.loqt_absmax_dq_workspace_bytes.argtypes = [_i64]
+lib.loqt_absmax_dq_compress.restype = _i
+lib.loqt_absmax_dq_compress.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.loqt_absmax_dq_expand.restype = _i
+lib.loqt_absmax_dq_expand.argtypes = [_vp, _vp, _vp, _i64, _vp, _vp]
 lib.loqt_set_path.restype = _i
 lib.loqt_set_path.argtypes = [_i]
 lib.loqt_resolved_path.restype = _i
@@ -316,6 +322,31 @@ def loqt_adam_step(B: torch.Tensor, grad: torch.Tensor, m: torch.Tensor, v: torc
     _check(lib.loqt_adam_step(B.data_ptr(), _pitch(B), B.shape[0], B.shape[1], grad.data_ptr(), dt, _pitch(grad),
                               m.data_ptr(), v.data_ptr(), _pitch(m), lr, beta1, beta2, eps, step, _stream()),
            "loqt_adam_step")
+
+
+def loqt_absmax_dq_compress(absmax: torch.Tensor):
+    """fp32 block scales (any shape, contiguous, taken flat) -> (codes uint8 [n], c1 float32 [ceil(n/256)],
+    mean float32 [1]), all on the device."""
+    a = absmax.reshape(-1)
+    n = a.numel()
+    dev = a.device
+    codes = torch.empty(n, dtype=torch.uint8, device=dev)
+    c1 = torch.empty((n + 255) // 256, dtype=torch.float32, device=dev)
+    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    ws = torch.empty(max(int(lib.loqt_absmax_dq_workspace_bytes(n)), 8), dtype=torch.uint8, device=dev)
+    _check(lib.loqt_absmax_dq_compress(a.data_ptr(), n, codes.data_ptr(), c1.data_ptr(), mean.data_ptr(),
+                                       *_ws_args(ws), _stream()), "loqt_absmax_dq_compress")
+    return codes, c1, mean
+
+
+def loqt_absmax_dq_expand(codes: torch.Tensor, c1: torch.Tensor, mean: torch.Tensor,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n = codes.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    _check(lib.loqt_absmax_dq_expand(codes.data_ptr(), c1.data_ptr(), mean.data_ptr(), n, out.data_ptr(), _stream()),
+           "loqt_absmax_dq_expand")
+    return out
 
 
 def loqt_merge_schedule(n: int, tau: float = 100.0, psi: float = 1.2, cap: int = 2500):

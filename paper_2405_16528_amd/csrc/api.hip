@@ -1147,6 +1147,30 @@ loqt_status loqt_merge_nq(loqt_bf16* W, int64_t ld_W, const loqt_bf16* P, int64_
     return LOQT_OK;
 }
 
+size_t loqt_absmax_dq_workspace_bytes(int64_t n) {
+    return n <= 0 ? 0 : round_up((size_t)dq_partials(n) * sizeof(double), 256);
+}
+
+loqt_status loqt_absmax_dq_compress(const float* absmax, int64_t n, uint8_t* codes8, float* c1, float* mean, void* ws,
+                                    size_t ws_bytes, void* hip_stream) {
+    if (!absmax || !codes8 || !c1 || !mean) return LOQT_INVALID_ARG;
+    if (n <= 0 || n > ((int64_t)1 << 40)) return LOQT_BAD_SHAPE;
+    if (!aligned(absmax, 4) || !aligned(c1, 4) || !aligned(mean, 4)) return LOQT_MISALIGNED;
+    LOQT_TRY(check_ws(ws, ws_bytes, loqt_absmax_dq_workspace_bytes(n)));
+    if (!aligned(ws, 8)) return LOQT_MISALIGNED;
+    LOQT_HIP(launch_dq_compress(absmax, n, codes8, c1, mean, reinterpret_cast<double*>(ws), (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+loqt_status loqt_absmax_dq_expand(const uint8_t* codes8, const float* c1, const float* mean, int64_t n, float* absmax_out,
+                                  void* hip_stream) {
+    if (!codes8 || !c1 || !mean || !absmax_out) return LOQT_INVALID_ARG;
+    if (n <= 0 || n > ((int64_t)1 << 40)) return LOQT_BAD_SHAPE;
+    if (!aligned(c1, 4) || !aligned(mean, 4) || !aligned(absmax_out, 4)) return LOQT_MISALIGNED;
+    LOQT_HIP(launch_dq_expand(codes8, c1, mean, n, absmax_out, (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
 loqt_status loqt_set_path(int path) {
     if (path < LOQT_PATH_AUTO || path > LOQT_PATH_FOLDED) return LOQT_INVALID_ARG;
     g_path = path;

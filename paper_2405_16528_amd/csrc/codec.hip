@@ -158,6 +158,125 @@ static int grid_for(int64_t work_items, int per_block) {
     return (int)b;
 }
 
+// ---------------------------------------------------------------------------------------
+// Double quantisation of the block scales (paper sec. 2.4: "the quantization state itself is
+// re-quantized"; the paper gives no format, the one used is stated in include/loqt.h):
+// scales minus their mean, in blocks of 256 with one fp32 constant c1 = max |d| per block, each
+// stored as an 8-bit float (1-4-3, bias 7, no infinities, largest value 448).
+// ---------------------------------------------------------------------------------------
+constexpr int DQ_BLOCK = 256;
+constexpr int DQ_CHUNK = 4096;  // scales summed by one work-group of the mean's first stage
+
+// fixed-order sum of the 256 per-thread values of a work-group (same result on every run)
+__device__ __forceinline__ double block_sum_f64(double v, double* sh) {
+    sh[threadIdx.x] = v;
+    __syncthreads();
+#pragma unroll
+    for (int s = 128; s > 0; s >>= 1) {
+        if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__global__ __launch_bounds__(256) void dq_partial_sums_kernel(const float* __restrict__ a, int64_t n,
+                                                              double* __restrict__ partial) {
+    __shared__ double sh[256];
+    const int64_t base = (int64_t)blockIdx.x * DQ_CHUNK;
+    double acc = 0.0;
+#pragma unroll
+    for (int i = 0; i < DQ_CHUNK / 256; ++i) {
+        const int64_t j = base + i * 256 + threadIdx.x;
+        if (j < n) acc += (double)a[j];
+    }
+    const double tot = block_sum_f64(acc, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(256) void dq_mean_kernel(const double* __restrict__ partial, int64_t nparts, int64_t n,
+                                                      float* __restrict__ mean) {
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (int64_t j = threadIdx.x; j < nparts; j += 256) acc += partial[j];
+    const double tot = block_sum_f64(acc, sh);
+    if (threadIdx.x == 0) *mean = (float)(tot / (double)n);
+}
+
+// fp32 -> E4M3 code, round to nearest even, |u| <= 448 by construction (saturates anyway)
+__device__ __forceinline__ uint32_t e4m3_encode(float u) {
+    const uint32_t bits = __float_as_uint(u);
+    const uint32_t sign = (bits >> 24) & 0x80u;
+    const float a = fabsf(u);
+    uint32_t code;
+    if (a < 0.03125f) {
+        // below 2^-5 the representable values are the multiples of 2^-9 (subnormals and the first binade)
+        code = (uint32_t)__float2int_rn(a * 512.0f);
+    } else {
+        const uint32_t ab = bits & 0x7fffffffu;
+        const uint32_t r = ab + 0x7ffffu + ((ab >> 20) & 1u);  // round the 23-bit mantissa to 3 bits, ties to even
+        code = (r >> 20) - (120u << 3);                        // exponent bias 127 -> 7
+        if (code > 0x7eu) code = 0x7eu;
+    }
+    return code | sign;
+}
+__device__ __forceinline__ float e4m3_decode(uint32_t code) {
+    const uint32_t e = (code >> 3) & 15u, m = code & 7u;
+    const float mag = e == 0 ? (float)m * 0.001953125f : __uint_as_float(((e + 120u) << 23) | (m << 20));
+    return (code & 0x80u) ? -mag : mag;
+}
+
+// one work-group per block of 256 scales
+__global__ __launch_bounds__(256) void dq_compress_kernel(const float* __restrict__ a, int64_t n,
+                                                          const float* __restrict__ mean_p, uint8_t* __restrict__ codes,
+                                                          float* __restrict__ c1) {
+    __shared__ float shm[4];
+    const int64_t j = (int64_t)blockIdx.x * DQ_BLOCK + threadIdx.x;
+    const float mean = *mean_p;
+    const float d = j < n ? a[j] - mean : 0.f;
+    float m = fabsf(d);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if ((threadIdx.x & 63) == 0) shm[threadIdx.x >> 6] = m;
+    __syncthreads();
+    const float c = fmaxf(fmaxf(shm[0], shm[1]), fmaxf(shm[2], shm[3]));
+    if (threadIdx.x == 0) c1[blockIdx.x] = c;
+    if (j < n) {
+        uint32_t code = (__float_as_uint(d) >> 24) & 0x80u;  // block of equal scales: +-0
+        if (c > 0.f) {
+            const float t = d / c;  // correctly rounded division
+            code = e4m3_encode(t * 448.0f);
+        }
+        codes[j] = (uint8_t)code;
+    }
+}
+
+__global__ __launch_bounds__(256) void dq_expand_kernel(const uint8_t* __restrict__ codes, const float* __restrict__ c1,
+                                                        const float* __restrict__ mean_p, int64_t n,
+                                                        float* __restrict__ out) {
+    const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    const float v = e4m3_decode(codes[j]);
+    float t = v * c1[j / DQ_BLOCK];
+    t = t / 448.0f;
+    out[j] = t + *mean_p;
+}
+
+hipError_t launch_dq_compress(const float* absmax, int64_t n, uint8_t* codes, float* c1, float* mean, double* partial,
+                              hipStream_t st) {
+    const int64_t nparts = (n + DQ_CHUNK - 1) / DQ_CHUNK;
+    hipLaunchKernelGGL(dq_partial_sums_kernel, dim3((unsigned)nparts), dim3(256), 0, st, absmax, n, partial);
+    hipLaunchKernelGGL(dq_mean_kernel, dim3(1), dim3(256), 0, st, partial, nparts, n, mean);
+    hipLaunchKernelGGL(dq_compress_kernel, dim3((unsigned)((n + DQ_BLOCK - 1) / DQ_BLOCK)), dim3(256), 0, st, absmax, n,
+                       mean, codes, c1);
+    return hipGetLastError();
+}
+hipError_t launch_dq_expand(const uint8_t* codes, const float* c1, const float* mean, int64_t n, float* out,
+                            hipStream_t st) {
+    hipLaunchKernelGGL(dq_expand_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, codes, c1, mean, n, out);
+    return hipGetLastError();
+}
+int64_t dq_partials(int64_t n) { return (n + DQ_CHUNK - 1) / DQ_CHUNK; }
+
 hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t ld_w, uint8_t* codes,
                            float* absmax, int64_t ld_q, hipStream_t st) {
     TimedLaunch tl(SLOT_QUANTIZE, st);

@@ -158,6 +158,14 @@ hipError_t launch_adam(uint16_t* B, int64_t ld_B, const void* g, int g_dtype, in
 hipError_t launch_f32_to_bf16(const float* in, int64_t rows, int64_t cols, int64_t ld_in, uint16_t* out,
                               int64_t ld_out, hipStream_t st);
 
+// double-quantised block scales: codes (1 byte per scale), c1 (one fp32 per 256 scales), mean (one fp32);
+// partial: dq_partials(n) doubles of scratch
+hipError_t launch_dq_compress(const float* absmax, int64_t n, uint8_t* codes, float* c1, float* mean, double* partial,
+                              hipStream_t st);
+hipError_t launch_dq_expand(const uint8_t* codes, const float* c1, const float* mean, int64_t n, float* out,
+                            hipStream_t st);
+int64_t dq_partials(int64_t n);
+
 // operand storage kinds of the GEMM
 enum OpKind {
     KC_BF16 = 0,  // bf16, rows x K, K contiguous

@@ -27,6 +27,7 @@ def test_every_declared_symbol_is_exported(lib):
             "loqt_merge_requant_batched", "loqt_workspace_bytes", "loqt_status_string", "loqt_set_path",
             "loqt_init_compensate", "loqt_linear_fwd_right", "loqt_linear_bwd_right",
             "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule",
+            "loqt_absmax_dq_workspace_bytes", "loqt_absmax_dq_compress", "loqt_absmax_dq_expand",
             "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq", "loqt_linear_fwd_save",
             "loqt_linear_bwd_saved"} <= names
     for n in names:
@@ -135,6 +136,19 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.loqt_adam_step(P, 512, 128, 512, P, 7, 512, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 1   # dtype
     assert lib.loqt_adam_step(P, 512, 128, 512, P, 0, 100, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 2   # ld_grad
     assert lib.loqt_adam_step(P, 512, 128, 512, None, 0, 512, P, P, 512, 1e-3, 0.9, 0.999, 1e-8, 1, None) == 1
+    dqc, dqe = lib.loqt_absmax_dq_compress, lib.loqt_absmax_dq_expand
+    dqc.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    dqe.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    lib.loqt_absmax_dq_workspace_bytes.restype = C.c_size_t
+    lib.loqt_absmax_dq_workspace_bytes.argtypes = [C.c_int64]
+    assert lib.loqt_absmax_dq_workspace_bytes(0) == 0 and lib.loqt_absmax_dq_workspace_bytes(4096 * 64) >= 64 * 8
+    assert dqc(None, 1000, P, P, P, P, ws, None) == 1
+    assert dqc(P, 0, P, P, P, P, ws, None) == 2
+    assert dqc(P + 2, 1000, P, P, P, P, ws, None) == 3
+    assert dqc(P, 1000, P, P, P, P, 0, None) == 4
+    assert dqe(P, P, None, 1000, P, None) == 1
+    assert dqe(P, P, P, -5, P, None) == 2
+    assert dqe(P, P + 1, P, 1000, P, None) == 3
     assert lib.loqt_merge_schedule(100.0, 1.2, 2500, 4, None) == 1
     assert lib.loqt_merge_schedule(100.0, 0.5, 2500, 0, (C.c_int64 * 1)()) == 1                            # psi < 1
 
