@@ -208,7 +208,7 @@ loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *desc
 
 /*
  * Right-side projection variant (sec. 2.2: the one-sided projection is P^T G when the weight has
- * no more rows than columns and G Q otherwise; "if m > n the same reasoning holds for Q^T").  The
+ * no more rows than columns and G Q otherwise, with the same argument for the right-side factor).  The
  * fixed NF4 projection sits on the input side and the trainable 16-bit factor on the output side:
  *     W_eff = deq(Wq) + s * Bp deq(Qq)^T        Wq: out x in,  Qq: in x r,  Bp: out x r (pitch ld_Bp)
  *   loqt_linear_fwd_right    y  = x W_eff^T  = x deq(Wq)^T + s (x deq(Qq)) Bp^T
@@ -305,7 +305,7 @@ loqt_status loqt_merge_dense(const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq, con
 
 /*
  * loqt_absmax_dq_compress / loqt_absmax_dq_expand -- double quantisation of the block scales (sec. 2.4:
- * "the quantization state itself is re-quantized for further efficiency", following the NF4 paper).
+ * the quantisation state is itself quantised again, as in the NF4 paper).
  * The paper gives no format; the one implemented is the cited method's description: the scales, being
  * positive, have their mean subtracted and are stored as 8-bit floats in blocks of 256 with one fp32
  * constant per block.  With M[0..n) the fp32 scales of an NF4 matrix taken as a flat array (absmax with
@@ -355,7 +355,7 @@ loqt_status loqt_adam_step(loqt_bf16 *B, int64_t ld_B, int64_t rows, int64_t col
  * ablation of update intervals caps them at 2500).  HOST function, no GPU work:
  *     gap_i = min(cap, floor(tau + psi^i)),   steps_out[i] = gap_0 + ... + gap_i,   i = 0..n-1
  * (the text also prints T_i = tau + psi^i for the steps themselves; growing intervals are the
- * reading that matches "starting at 100 ... up to 2500").  steps_out: HOST array of n entries.
+ * reading that matches the ablation, whose intervals start at 100 and reach 2500).  steps_out: HOST array of n entries.
  */
 loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int64_t *steps_out);
 

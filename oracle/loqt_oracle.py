@@ -18,8 +18,8 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
   merge  (Alg. 1 line 5, sec. 2.4, sec. 2.5 first paragraph):
       W_new = deq(W_q) + s * deq(P_q) @ B ;  (codes', absmax') = q_NF4(W_new)
 
-  right  (sec. 2.2 first paragraph: "we compute P^T G if m <= n and G Q otherwise ... if
-          m > n the same reasoning holds for Q^T"): the projection sits on the input side,
+  right  (sec. 2.2 first paragraph: the gradient is projected from the left, P^T G, when the weight
+          has no more rows than columns, and from the right, G Q, otherwise): the projection sits on the input side,
       W_eff = deq(W_q) + s * Bp @ deq(Q_q)^T   Q in x r fixed (NF4), Bp out x r trainable;
       y = x @ W_eff^T ; dx = dy @ W_eff ; dBp = s * dy^T @ (x @ deq(Q_q))
   nq     (the paper's LoQT-nq, "no quantization": the same layer with W and P kept in 16 bits):
@@ -31,7 +31,7 @@ Everything is the plain definition, evaluated in numpy float64 in one pass:
   step   (Alg. 1 line 9: B_{t+1} = B_t - rho(G^B_t), rho = Adam; sec. 2.5 last paragraph and
           the hyper-parameter appendix: W is updated at steps T_i whose gaps are tau + psi^i).
 
-  dq     (sec. 2.4: "the quantization state itself is re-quantized ... following [QLoRA]"): the fp32
+  dq     (sec. 2.4 says that the quantisation state is itself quantised again, as in the NF4 paper): the fp32
           block scales of an NF4 matrix are themselves stored in 8 bits.  PARITY UNPINNED BY THE PAPER:
           it gives no format.  Reading taken (the cited method's own description: the scales, being
           positive, have their mean subtracted and are quantised to 8-bit floats in blocks of 256 with one
@@ -67,11 +67,13 @@ notes of the repository):
     m = b1 m + (1-b1) g, v = b2 v + (1-b2) g^2, B -= lr (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps);
     no weight decay; pinned against torch.optim.Adam.
   * update schedule: the text gives T_i = tau + psi^i once as the steps themselves and once
-    (appendix, and the ablation's "starting at 100 ... up to 2500") as growing intervals; intervals
+    (appendix, and the ablation, whose intervals start at 100 and grow up to 2500) as growing intervals; intervals
     are the reading taken: gap_i = min(cap, floor(tau + psi^i)), T_i = gap_0 + ... + gap_i.
 Parity status: every function below is pinned by tests/test_oracle_*.py against
 closed forms, brute force in rational arithmetic, library routines and
-invariants; none is "parity unpinned".
+invariants.  One group is PARITY UNPINNED by the paper: absmax_dq_compress /
+absmax_dq_expand / e4m3_* (the paper gives no format for the re-quantised scales; the
+arithmetic of the reading stated above is pinned, the reading itself cannot be).
 """
 from __future__ import annotations
 

@@ -159,8 +159,8 @@ static int grid_for(int64_t work_items, int per_block) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Double quantisation of the block scales (paper sec. 2.4: "the quantization state itself is
-// re-quantized"; the paper gives no format, the one used is stated in include/loqt.h):
+// Double quantisation of the block scales (paper sec. 2.4 says that the quantisation state is
+// itself quantised again; it gives no format, the one used is stated in include/loqt.h):
 // scales minus their mean, in blocks of 256 with one fp32 constant c1 = max |d| per block, each
 // stored as an 8-bit float (1-4-3, bias 7, no infinities, largest value 448).
 // ---------------------------------------------------------------------------------------

@@ -1,5 +1,5 @@
-"""Pins of the oracle's double-quantised block scales (paper sec. 2.4: "the quantization state itself is
-re-quantized").  The paper gives no format (parity unpinned by the paper); what is pinned here is the oracle's
+"""Pins of the oracle's double-quantised block scales (paper sec. 2.4: the quantisation state is itself
+quantised again).  The paper gives no format (parity unpinned by the paper); what is pinned here is the oracle's
 arithmetic for the reading it states: the 8-bit float against a library cast, round-trip bounds, closed forms."""
 import numpy as np
 import pytest
