@@ -35,6 +35,8 @@ namespace loqt {
 
 namespace {
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 constexpr int BK = 64;
 constexpr int ROWB = 128;  // bytes of one LDS row (64 bf16)
 
@@ -110,6 +112,19 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    // The plain bf16 products (y, dx, Z: most of a training step) use v_mfma_f32_16x16x32_bf16 instead: the same
+    // flops per cycle and the same LDS bytes, but a quarter of the accumulator registers read and written per
+    // instruction, which on this power-limited part is worth a few per cent of clock.  Their accumulators:
+    // 16x16 tiles (ti, tj) of the wave tile, lane = row ti*16 + (lane & 15), register r = column tj*16 + 4*(lane >> 4) + r.
+    constexpr bool MF16 = EPI == EPI_BF16;
+    constexpr int TM2 = MF16 ? 2 * TM : 1, TN2 = MF16 ? 2 * TN : 1;
+    f32x4 acc16[TM2][TN2];
+#pragma unroll
+    for (int i = 0; i < TM2; ++i)
+#pragma unroll
+        for (int j = 0; j < TN2; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc16[i][j][e] = 0.f;
 
     // merge with 128x128 tiles: the old codes and scales of this lane's 64-blocks are fetched here, ahead of the
     // product, so that the epilogue does not start with a round trip to memory (18 registers; the 256-wide tiles
@@ -150,6 +165,9 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     // scalar-base form and no 64-bit address arithmetic runs on the vector unit.
     // A k-tile that is not full (the last one of a K segment whose extent is not a multiple of 64) takes the
     // path below instead: through registers, elements past K zeroed, ordinary LDS stores.
+    // XOR of the chunk index of k row kk of a row-contiguous tile.  The 16x16x32 form reads k rows kk and kk + 8 in
+    // the same half-wave (lanes 0-15 and 16-31), so there bit 3 of kk moves the row by a further 32 bytes.
+    auto rc_swz = [](int kk) { return (4 * (kk & 3)) ^ (MF16 ? 2 * ((kk >> 3) & 1) : 0); };
     auto tail_operand = [&](auto rc_tag, auto br_tag, const void* optr, int64_t old, int orows, int oK, int row0, int k0,
                             char* tile) {
         constexpr bool RC = decltype(rc_tag)::value;
@@ -186,14 +204,14 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             constexpr int CPR = BR / 8;       // chunks per k row
             constexpr int KPI = 256 / CPR;    // k rows covered by one pass of the 256 threads
             const int kq = tid / CPR;         // k of chunk i is i*KPI + kq  (KPI is a multiple of 4)
-            const int logical = (tid % CPR) ^ (4 * (kq & 3));
             const int clast = (((orows - 1) >> 3) << 3) - row0;  // columns past the end: any valid chunk
             const char* sbase = reinterpret_cast<const char*>(optr) + ((int64_t)k0 * old + row0) * 2;
-            const uint32_t off0 = (uint32_t)kq * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
 #pragma unroll 1
             for (int i = 0; i < NC; ++i) {
+                const int logical = (tid % CPR) ^ rc_swz(i * KPI + kq);
+                const uint32_t off = (uint32_t)(i * KPI + kq) * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
                 uint4 v = make_uint4(0, 0, 0, 0);
-                if (i * KPI + kq < kleft) v = *reinterpret_cast<const uint4*>(sbase + (off0 + (uint32_t)(i * KPI) * ld2));
+                if (i * KPI + kq < kleft) v = *reinterpret_cast<const uint4*>(sbase + off);
                 *reinterpret_cast<uint4*>(tile + i * 4096 + tid * 16) = v;
             }
         }
@@ -294,11 +312,12 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 constexpr int CPR = BR / 8;
                 constexpr int KPI = 256 / CPR;
                 const int kq = tid / CPR;
-                const int logical = (tid % CPR) ^ (4 * (kq & 3));
                 const int clast = (((orows - 1) >> 3) << 3) - row0;
 #pragma unroll
-                for (int i = 0; i < NC; ++i)
+                for (int i = 0; i < NC; ++i) {
+                    const int logical = (tid % CPR) ^ rc_swz(kq + i * KPI);
                     off[i] = (uint32_t)(kq + i * KPI) * ld2 + (uint32_t)min(logical * 8, clast) * 2u;
+                }
                 base = reinterpret_cast<const char*>(optr) + ((int64_t)k0 * old + row0) * 2;
                 step = (int64_t)BK * old * 2;
             }
@@ -378,6 +397,87 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
+        // ---- the same loop for the 16x16x32 form: two k32 steps per k-tile, two MFMAs per slot.  Step A: the
+        // MFMAs of k32 step 0, the reads of step 1 after the first slots, the second half of tile kt+1 after the last
+        // ones.  Step B: the MFMAs of step 1; the barrier sits in its middle, and after it come the reads of the next
+        // tile's step 0 and the first half of tile kt+2.
+        constexpr int NM2 = TM2 * TN2, NS2 = NM2 / 2, NU2 = TM2 + TN2;
+        const int frow16 = lane & 15, q4 = lane >> 4;
+        uint32_t a_ko[2], b_ko[2];  // K-contiguous tiles: byte offset of this lane's fragment row and chunk per k32 step
+        int a_rc16[ARC ? TM2 : 1], b_rc16[BRC ? TN2 : 1];
+        bf16x8 fa16[2][TM2], fb16[2][TN2];
+        if constexpr (MF16) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                const int coff = ((4 * ks + q4) ^ swz(frow16)) << 4;
+                a_ko[ks] = (uint32_t)((wm * Cfg::WTM + frow16) * ROWB + coff);
+                b_ko[ks] = (uint32_t)(BM * ROWB + (wn * Cfg::WTN + frow16) * ROWB + coff);
+            }
+            // row-contiguous tiles: within a group of 16 lanes, lane 4*jj + q supplies the address of k row
+            // 8*(lane >> 4) + jj, columns 4q..4q+3, and receives the four k of column (lane & 15)
+            const int jj = (lane >> 2) & 3, q = lane & 3;
+            if constexpr (ARC) {
+#pragma unroll
+                for (int u = 0; u < TM2; ++u) {
+                    const int chunk = ((wm * Cfg::WTM + u * 16) >> 3) + (q >> 1);
+                    a_rc16[u] = (8 * q4 + jj) * (BM * 2) + ((chunk ^ rc_swz(8 * q4 + jj)) << 4) + (q & 1) * 8;
+                }
+            }
+            if constexpr (BRC) {
+#pragma unroll
+                for (int u = 0; u < TN2; ++u) {
+                    const int chunk = ((wn * Cfg::WTN + u * 16) >> 3) + (q >> 1);
+                    b_rc16[u] = BM * ROWB + (8 * q4 + jj) * (BN * 2) + ((chunk ^ rc_swz(8 * q4 + jj)) << 4) + (q & 1) * 8;
+                }
+            }
+        }
+        // fragment u (A fragments first) of k32 step ks of the tile at `stage` into buffer nb
+        auto rd16 = [&](int ks, int nb, int u, const char* stage) {
+            if (u < TM2) {
+                if constexpr (ARC) fa16[nb][u] = read_tr(stage + a_rc16[u] + 32 * ks * (BM * 2), BM * 2);
+                else fa16[nb][u] = *reinterpret_cast<const bf16x8*>(stage + a_ko[ks] + u * 16 * ROWB);
+            } else {
+                const int j = u - TM2;
+                if constexpr (BRC) fb16[nb][j] = read_tr(stage + b_rc16[j] + 32 * ks * (BN * 2), BN * 2);
+                else fb16[nb][j] = *reinterpret_cast<const bf16x8*>(stage + b_ko[ks] + j * 16 * ROWB);
+            }
+        };
+        // slots S0..S1-1 (two MFMAs each) of a k32 step on fragment buffer CB.  RD: fragment reads of k32 step RKS of
+        // the tile at `rstage` into the other buffer, spread over the first slots of the range.  LD (0 / 1, or -1):
+        // the loads of that half of the tile at hotA / hotB into `lstage`, one per slot on the last slots.
+        auto slots16 = [&](auto cb_tag, auto s0_tag, auto s1_tag, auto rd_tag, auto rks_tag, auto ld_tag, const char* rstage,
+                           char* lstage, uint32_t live) {
+            constexpr int CB = decltype(cb_tag)::value, S0 = decltype(s0_tag)::value, S1 = decltype(s1_tag)::value;
+            constexpr bool RD = decltype(rd_tag)::value;
+            constexpr int RKS = decltype(rks_tag)::value, LD = decltype(ld_tag)::value;
+            constexpr int NSL = S1 - S0;
+            constexpr int RPS = (NU2 + NSL - 1) / NSL;                   // fragment reads per slot
+            constexpr int LPS16 = (NL + NSL - 1) / NSL;                  // loads per slot ...
+            constexpr int LSL = (NL + LPS16 - 1) / LPS16;                // ... on LSL slots ...
+            constexpr int LST = NSL >= 2 * LSL ? 2 : 1;                  // ... every LST-th of the last LST * LSL
+#pragma unroll
+            for (int sl = S0; sl < S1; ++sl) {
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int m = 2 * sl + e, i = m / TN2, j = m % TN2;
+                    acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb16[CB][j], fa16[CB][i], acc16[i][j], 0, 0, 0);
+                }
+                const int t = sl - S0;
+                if constexpr (RD) {
+#pragma unroll
+                    for (int u = t * RPS; u < (t + 1) * RPS && u < NU2; ++u) rd16(RKS, CB ^ 1, u, rstage);
+                }
+                if constexpr (LD >= 0) {
+                    const int tl = t - (NSL - LST * LSL);
+                    if (tl >= 0 && tl % LST == 0) {
+#pragma unroll
+                        for (int n = (tl / LST) * LPS16; n < (tl / LST + 1) * LPS16 && n < NL; ++n)
+                            hot_load(ld_tag, n, lstage, live);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
         using I0 = std::integral_constant<int, 0>;
         using I1 = std::integral_constant<int, 1>;
         using I2 = std::integral_constant<int, 2>;
@@ -410,7 +510,12 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             }
             wait_loads();
             __syncthreads();
-            load_frags(smem, 0, 0);
+            if constexpr (MF16) {
+#pragma unroll
+                for (int u = 0; u < NU2; ++u) rd16(0, 0, u, smem);
+            } else {
+                load_frags(smem, 0, 0);
+            }
             if (kt_begin + 1 < kt_end) {
                 hot_advance(kt_begin + 1);
                 if (is_tail(kt_begin + 1)) {
@@ -427,16 +532,25 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
             char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
             const uint32_t live2 = live_mask(kt + 2);
-            kstep(I0{}, I1{}, I1{}, cur, nxt, live1);  // + second half of tile kt+1
+            using SH = std::integral_constant<int, NS2 / 2>;
+            using SE = std::integral_constant<int, NS2>;
+            if constexpr (MF16) slots16(I0{}, I0{}, SE{}, std::true_type{}, I1{}, I1{}, cur, nxt, live1);
+            else kstep(I0{}, I1{}, I1{}, cur, nxt, live1);  // + second half of tile kt+1
             if (kt + 2 < kt_end) hot_advance(kt + 2);
-            kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
-            kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
+            if constexpr (MF16) {
+                slots16(I1{}, I0{}, SH{}, std::false_type{}, I0{}, NOLD{}, cur, nxt, 0);
+            } else {
+                kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
+                kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
+            }
             wait_loads();
             __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
             if (live2 == 0) {        // no tile kt+2, or a tail tile (rare)
                 if (kt + 2 < kt_end) tail_tile(kt + 2, cur);
             }
-            kstep(I1{}, I0{}, I0{}, nxt, cur, live2);  // + first half of tile kt+2 (harmless stale reads after the last tile)
+            // + first half of tile kt+2 (harmless stale reads after the last tile)
+            if constexpr (MF16) slots16(I1{}, SH{}, SE{}, std::true_type{}, I0{}, I0{}, nxt, cur, live2);
+            else kstep(I1{}, I0{}, I0{}, nxt, cur, live2);
             live1 = live2;
         }
     }
@@ -454,6 +568,17 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         }
         char* ebuf = smem + wave * (WTM * EPITCH);
         const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
+        if constexpr (MF16) {
+            const int frow16 = lane & 15, q4 = lane >> 4;
+#pragma unroll
+            for (int ti = 0; ti < TM2; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < TN2; ++tj) {
+                    const uint2 v = make_uint2(pack_bf16(alpha * acc16[ti][tj][0], alpha * acc16[ti][tj][1]),
+                                               pack_bf16(alpha * acc16[ti][tj][2], alpha * acc16[ti][tj][3]));
+                    *reinterpret_cast<uint2*>(ebuf + (ti * 16 + frow16) * EPITCH + (tj * 16 + 4 * q4) * 2) = v;
+                }
+        } else {
 #pragma unroll
         for (int ti = 0; ti < TM; ++ti)
 #pragma unroll
@@ -496,6 +621,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                     *reinterpret_cast<uint2*>(ebuf + (ti * 32 + frow) * EPITCH + (tj * 32 + 8 * g + 4 * h) * 2) = v;
                 }
             }
+        }
         // the region is private to the wave and LDS operations of one wave complete in order
         constexpr int CPR = WTN / 8;  // 16-byte chunks per row
         uint16_t* C = reinterpret_cast<uint16_t*>(part1 ? p.Cx : p.C);
