@@ -167,6 +167,18 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     // path below instead: through registers, elements past K zeroed, ordinary LDS stores.
     // XOR of the chunk index of k row kk of a row-contiguous tile.  The 16x16x32 form reads k rows kk and kk + 8 in
     // the same half-wave (lanes 0-15 and 16-31), so there bit 3 of kk moves the row by a further 32 bytes.
+    // XOR of the chunk index of row `row` of a K-contiguous tile.  A 16-byte LDS read is served in sets of
+    // 16 lanes, {0-3, 12-15, 20-23, 24-27} and {4-7, 8-11, 16-19, 28-31} of each half-wave (measured), and a row is
+    // half the banks.  In the 32x32x16 form a set holds 16 different rows of one chunk column pair; in the
+    // 16x16x32 form it holds rows 0-3 and 12-15 of one column and rows 4-11 of the next, which needs another map.
+    auto kc_swz = [](int row) {
+        if constexpr (MF16) {
+            const int e = (row >> 1) & 7;
+            return (e & 1) | ((e & 2) << 1) | ((e & 4) >> 1);
+        } else {
+            return swz(row);
+        }
+    };
     auto rc_swz = [](int kk) { return (4 * (kk & 3)) ^ (MF16 ? 2 * ((kk >> 3) & 1) : 0); };
     auto tail_operand = [&](auto rc_tag, auto br_tag, const void* optr, int64_t old, int orows, int oK, int row0, int k0,
                             char* tile) {
@@ -181,7 +193,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         const uint32_t ld2 = (uint32_t)old * 2u;  // row pitch in bytes (a tile spans < 2^32 bytes)
         if constexpr (!RC) {
             const int r0 = tid >> 3;
-            const int kc = (tid & 7) ^ swz(r0);
+            const int kc = (tid & 7) ^ kc_swz(r0);
             const int rlast = orows - 1 - row0;  // rows past the end: any valid row
             const char* sbase = reinterpret_cast<const char*>(optr) + ((int64_t)row0 * old + k0) * 2;
             const int nv = kleft - kc * 8;  // valid elements of this thread's chunk column
@@ -302,7 +314,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             const uint32_t ld2 = (uint32_t)old * 2u;
             if constexpr (!RC) {
                 const int r0 = tid >> 3;
-                const int kc = (tid & 7) ^ swz(r0);
+                const int kc = (tid & 7) ^ kc_swz(r0);
                 const int rlast = orows - 1 - row0;
 #pragma unroll
                 for (int i = 0; i < NC; ++i) off[i] = (uint32_t)min(i * 32 + r0, rlast) * ld2 + (uint32_t)kc * 16u;
@@ -409,7 +421,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         if constexpr (MF16) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const int coff = ((4 * ks + q4) ^ swz(frow16)) << 4;
+                const int coff = ((4 * ks + q4) ^ kc_swz(frow16)) << 4;
                 a_ko[ks] = (uint32_t)((wm * Cfg::WTM + frow16) * ROWB + coff);
                 b_ko[ks] = (uint32_t)(BM * ROWB + (wn * Cfg::WTN + frow16) * ROWB + coff);
             }
