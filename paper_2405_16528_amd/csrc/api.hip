@@ -560,13 +560,16 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
         const int64_t ldw = saved ? ld_saved : (int64_t)round_up(in, 8);
         LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_z, st, SLOT_PREPASS));
         const bool folded = dx && (saved || use_folded(T, out, in));
-        // Z rides along with dx (one product [dx | Z] over the shared operand dy) when its tiles fit
-        // into the last, partly empty round of 256x256 tiles of the dx product; otherwise its own launch
+        // Z rides along with dx (one product [dx | Z] over the shared operand dy) when that is estimated to
+        // take less time than the two launches: its tiles then fill a partly empty round of the dx product
         bool z_with_dx = false;
         if (folded) {
-            const int64_t tm = (T + 255) / 256;
-            const int64_t t_dx = tm * ((in + 255) / 256), t_both = t_dx + tm * ((r + 255) / 256);
-            z_with_dx = t_dx >= 224 && (t_both + 255) / 256 == (t_dx + 255) / 256;
+            const int64_t tm = (T + 255) / 256, tm128 = (T + 127) / 128;
+            const int64_t t_dx = tm * ((in + 255) / 256), t_z = tm * ((r + 255) / 256);
+            // Z alone: 256x256 tiles when they fill the chip, else 128x128 in rounds of 512
+            const double z_alone = t_z >= 224 ? plan_bf16_product(T, r, 0).cost
+                                              : 0.68 * (double)((tm128 * ((r + 127) / 128) + 511) / 512);
+            z_with_dx = t_dx >= 224 && plan_bf16_product(T, in, r).cost < plan_bf16_product(T, in, 0).cost + z_alone;
         }
         if (!z_with_dx) {
             // Z = s dy deq(P): deq(P) is out x r, i.e. K x rows

@@ -835,7 +835,28 @@ hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
 }
 
 }  // namespace
-extern int g_nt_tile_override;
+
+// Plan of a bf16-output product of M rows and N (+ Nx extra) columns in units of one round of 256x256 tiles
+// (256 tiles, one per compute unit).  A round of 128x128 tiles (512, two per compute unit) takes 0.68 of that,
+// measured, whether it is full or half full.  n1 > 0: the first n1 columns as 256x256 tiles in whole rounds, the
+// rest and the extra columns as 128x128 tiles.
+BF16Plan plan_bf16_product(int64_t M, int64_t N, int64_t Nx) {
+    auto cdiv = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
+    const int64_t tm = cdiv(M, 256), tn = cdiv(N, 256), tnx = cdiv(Nx, 256);
+    BF16Plan plan;
+    plan.n1 = 0;
+    plan.cost = (double)cdiv(tm * (tn + tnx), 256);
+    const int64_t whole = tm * tn / 256;
+    const int64_t c1 = whole * 256 / tm;  // tile columns of the first launch
+    if (whole >= 1 && c1 > 0 && c1 < tn && whole * 256 - c1 * tm < 32) {
+        const int64_t n1 = c1 * 256;
+        const int64_t tiles_b = cdiv(M, 128) * (cdiv(N - n1, 128) + cdiv(Nx, 128));
+        const double cost = (double)whole + 0.68 * (double)cdiv(tiles_b, 512);
+        if (cost < plan.cost) plan.cost = cost, plan.n1 = (int)n1;
+    }
+    return plan;
+}
+
 namespace {
 
 template <int EPI, bool ARC, bool BRC>
@@ -860,17 +881,15 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
         choice = (light && tiles(256, 256) >= 224) ? 1 : 3;
     }
     if constexpr (EPI == EPI_BF16) {
-        // 256x256 tiles run in rounds of one tile per compute unit.  When the last round would be
-        // less than half full, the tile columns that fill whole rounds go out as one launch and the
-        // remaining columns as a second launch of 128x128 tiles, which takes about half a round.
-        const int64_t tm = (p.M + 255) / 256, tn = (p.N + 255) / 256, total = tm * tn;
-        const int64_t whole = total / 256, rest = total - whole * 256;
-        const int64_t c1 = whole * 256 / tm;  // tile columns of the first launch
-        if (g_nt_tile_override == 0 && choice == 1 && p.Nx == 0 && whole >= 2 && rest > 0 && rest < 128 &&
-            c1 > 0 && c1 < tn && (whole * 256 - c1 * tm) < 32) {
-            const int n1 = (int)c1 * 256;
+        // 256x256 tiles run in rounds of one tile per compute unit.  When the last round would be mostly
+        // empty, the tile columns that fill whole rounds go out as one launch and the remaining columns
+        // (with the extra columns Nx, if any) as a second launch of 128x128 tiles.
+        const BF16Plan plan = plan_bf16_product(p.M, p.N, p.Nx);
+        if (g_nt_tile_override == 0 && choice == 1 && plan.n1 > 0) {
+            const int n1 = plan.n1;
             GemmParams a = p, b = p;
             a.N = n1;
+            a.Nx = 0;
             for (int seg = 0; seg < 2; ++seg) {
                 if (p.A[seg].K == 0) continue;
                 a.B[seg].rows = min(p.B[seg].rows, n1);

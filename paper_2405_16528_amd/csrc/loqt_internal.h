@@ -231,5 +231,12 @@ int gemm_db_splits(int64_t T, int64_t r, int64_t in);
 hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st);
 // tuning aid for benchmarks: 0 = choose by shape, 1 = 256x256, 2 = 256x128, 3 = 128x128 tiles
 extern int g_nt_tile_override;
+// how launch_gemm_nt lays out a bf16-output product (EPI_BF16) that is large enough for 256x256 tiles, and its
+// estimated duration in rounds of such tiles
+struct BF16Plan {
+    int n1;       // > 0: columns that go out as 256x256 tiles; the rest (and Nx) follow as 128x128 tiles
+    double cost;
+};
+BF16Plan plan_bf16_product(int64_t M, int64_t N, int64_t Nx);
 
 }  // namespace loqt
