@@ -112,11 +112,12 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-    // The plain bf16 products (y, dx, Z: most of a training step) use v_mfma_f32_16x16x32_bf16 instead: the same
-    // flops per cycle and the same LDS bytes, but a quarter of the accumulator registers read and written per
-    // instruction, which on this power-limited part is worth a few per cent of clock.  Their accumulators:
+    // The plain bf16 products on 256x256 tiles (y, dx: most of a training step) use v_mfma_f32_16x16x32_bf16
+    // instead: the same flops per cycle and the same LDS bytes, but a quarter of the accumulator registers read and
+    // written per instruction, which on this power-limited part is worth a few per cent of clock (measured: 5 %
+    // with both operands K-contiguous, 1 % with B stored K x rows; on 128x128 tiles nothing, or a loss).  Their accumulators:
     // 16x16 tiles (ti, tj) of the wave tile, lane = row ti*16 + (lane & 15), register r = column tj*16 + 4*(lane >> 4) + r.
-    constexpr bool MF16 = EPI == EPI_BF16;
+    constexpr bool MF16 = EPI == EPI_BF16 && BM == 256 && BN == 256;
     constexpr int TM2 = MF16 ? 2 * TM : 1, TN2 = MF16 ? 2 * TN : 1;
     f32x4 acc16[TM2][TN2];
 #pragma unroll
