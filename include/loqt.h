@@ -384,6 +384,18 @@ loqt_status loqt_set_path(int path);
 int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in);
 
 /*
+ * Tile-shape option (process-wide, not thread-safe; for tests and tuning).  The products of the
+ * pre-pass family (every product of the layer calls of sec. 2.2 / 2.4 and the merge of Alg. 1 line 5
+ * when it takes that path) run on work-group tiles of 256x256, 256x128 or 128x128 outputs, chosen from
+ * the sizes.  LOQT_TILE_AUTO keeps that choice; the other values force one shape for every such product
+ * whatever its size (the compensation step of Alg. 2 and the dense merge always use 128x128).  All
+ * shapes compute the same quantities; results differ only in summation order.  Returns
+ * LOQT_INVALID_ARG for any other value.
+ */
+enum { LOQT_TILE_AUTO = 0, LOQT_TILE_256x256 = 1, LOQT_TILE_256x128 = 2, LOQT_TILE_128x128 = 3 };
+loqt_status loqt_set_tile(int tile);
+
+/*
  * Optional per-kernel timing (diagnostics for benchmarks; off by default).
  * While enabled, every kernel launch of the library is bracketed by HIP events recorded on
  * the launch stream.  loqt_timing_read synchronises with the recorded events and returns,

@@ -25,6 +25,7 @@ F32, BF16 = 0, 1
 OP_FWD, OP_BWD, OP_MERGE, OP_INIT, OP_FWD_RIGHT, OP_BWD_RIGHT, OP_MERGE_RIGHT = 0, 1, 2, 3, 4, 5, 6
 OP_FWD_NQ, OP_BWD_NQ = 7, 8
 PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
+TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128 = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
                 4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
 
@@ -102,6 +103,8 @@ lib.loqt_absmax_dq_expand.restype = _i
 lib.loqt_absmax_dq_expand.argtypes = [_vp, _vp, _vp, _i64, _vp, _vp]
 lib.loqt_set_path.restype = _i
 lib.loqt_set_path.argtypes = [_i]
+lib.loqt_set_tile.restype = _i
+lib.loqt_set_tile.argtypes = [_i]
 lib.loqt_resolved_path.restype = _i
 lib.loqt_resolved_path.argtypes = [_i, _i64, _i64, _i64]
 lib.loqt_timing_enable.restype = None
@@ -375,6 +378,11 @@ def loqt_init_compensate(W: torch.Tensor, P: torch.Tensor, s: float, iters: int,
 def set_path(path: int) -> None:
     """PATH_AUTO, PATH_FUSED or PATH_PREPASS (process-wide)."""
     _check(lib.loqt_set_path(path), "loqt_set_path")
+
+
+def set_tile(tile: int) -> None:
+    """TILE_AUTO, TILE_256x256, TILE_256x128 or TILE_128x128 (process-wide; tests and tuning)."""
+    _check(lib.loqt_set_tile(tile), "loqt_set_tile")
 
 
 def resolved_path(op: int, T: int, out: int, inp: int) -> int:

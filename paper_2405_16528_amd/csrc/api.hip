@@ -1180,6 +1180,12 @@ loqt_status loqt_set_path(int path) {
     return LOQT_OK;
 }
 
+loqt_status loqt_set_tile(int tile) {
+    if (tile < LOQT_TILE_AUTO || tile > LOQT_TILE_128x128) return LOQT_INVALID_ARG;
+    g_nt_tile_override = tile;
+    return LOQT_OK;
+}
+
 void loqt_timing_enable(int on) {
     if (on) {
         if (!g_timing.begin) {

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
             "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule",
             "loqt_absmax_dq_workspace_bytes", "loqt_absmax_dq_compress", "loqt_absmax_dq_expand",
             "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq", "loqt_linear_fwd_save",
-            "loqt_linear_bwd_saved"} <= names
+            "loqt_linear_bwd_saved", "loqt_set_tile"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -113,6 +113,8 @@ def test_bad_arguments_are_rejected_before_launch(lib):
     assert lib.loqt_merge_requant_batched(0, None, P, ws, None) == 0                   # nothing to do
     assert lib.loqt_set_path(9) == 1
     assert lib.loqt_set_path(L.PATH_AUTO) == 0
+    assert lib.loqt_set_tile(4) == 1 and lib.loqt_set_tile(-1) == 1
+    assert lib.loqt_set_tile(L.TILE_AUTO) == 0
 
     Qm = L.NF4MatC(P, P, 512, 128, 128)   # in x r
     Qbad = L.NF4MatC(P, P, 256, 128, 128)  # rows differ from W's columns
