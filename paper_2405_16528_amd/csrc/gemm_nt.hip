@@ -50,7 +50,7 @@ __device__ __forceinline__ uint32_t nib4(uint32_t word, int e) {
     return (word >> (8 * (e >> 1) + ((e & 1) ? 0 : 4))) & 15u;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, int NS = 2>
 struct NtCfg {
     static constexpr int TM = BM / 64, TN = BN / 64;   // 32x32 tiles per wave
     static constexpr int WTM = BM / 2, WTN = BN / 2;   // wave tile
@@ -59,14 +59,14 @@ struct NtCfg {
     static constexpr int NCHA = BM / 32;               // of which belong to A
     static constexpr int NCHB = BN / 32;               // and to B
     static constexpr int EPITCH = WTN * 2 + 8;         // staging pitch of the bf16 epilogue
-    static constexpr int SMEM_MAIN = 2 * STAGE;
+    static constexpr int SMEM_MAIN = NS * STAGE;       // NS stages: tiles kt .. kt+NS-1 are in LDS or in flight
     static constexpr int SMEM_EPI = 4 * WTM * EPITCH;
     static constexpr int SMEM = (SMEM_MAIN > SMEM_EPI ? SMEM_MAIN : SMEM_EPI) + 64;
 };
 
-template <int BM, int BN, int EPI, bool ARC, bool BRC>
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
 __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
-    using Cfg = NtCfg<BM, BN>;
+    using Cfg = NtCfg<BM, BN, NS>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE;
     constexpr int NM = TM * TN;  // MFMAs per k16 step
     constexpr int NL = Cfg::NCH / 2;                    // direct loads of half a k-tile
@@ -374,7 +374,6 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 : "v"(o), "s"(base), "s"(dst), "s"(live)
                 : "memory");
         };
-        auto wait_loads = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
         // fragment u (A fragments first) of k16 step ks of the tile at `stage` into buffer nb
         auto read_unit = [&](int ks, int nb, int u, const char* stage) {
             const int coff = ((2 * ks) ^ fsw) << 4;
@@ -512,16 +511,31 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             return m;
         };
         auto is_tail = [&](int t) { return t == tail0 || t == tail1; };
+        // The ring of NS stages: tile t lives in stage (t - kt_begin) % NS.  At the top of iteration kt the tiles
+        // kt .. kt+NS-2 are in LDS or on their way, and so is the first half of tile kt+NS-1.
+        auto wait_loads = [&](bool later_live) {
+            // tile kt+1 must have landed.  Loads return in order, so it is enough that no more are outstanding
+            // than were issued after it: the NS-2 whole tiles kt+2 .. kt+NS-1 -- provided all of those went out
+            // as direct loads (a masked load may not count, a tail tile is stored through registers)
+            if (NS > 2 && later_live) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * Cfg::NCH) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        };
         if (kt_begin < kt_end) {
             hot_setup(kt_begin);
-            if (is_tail(kt_begin)) {
-                tail_tile(kt_begin, smem);
-            } else {
-                const uint32_t live = live_mask(kt_begin);
 #pragma unroll
-                for (int n = 0; n < Cfg::NCH; ++n) hot_load(I2{}, n, smem, live);
+            for (int t = 0; t < NS - 1; ++t) {
+                if (kt_begin + t < kt_end) {
+                    if (t > 0) hot_advance(kt_begin + t);
+                    if (is_tail(kt_begin + t)) {
+                        tail_tile(kt_begin + t, smem + t * STAGE);
+                    } else {
+                        const uint32_t live = live_mask(kt_begin + t);
+#pragma unroll
+                        for (int n = 0; n < Cfg::NCH; ++n) hot_load(I2{}, n, smem + t * STAGE, live);
+                    }
+                }
             }
-            wait_loads();
+            wait_loads(false);
             __syncthreads();
             if constexpr (MF16) {
 #pragma unroll
@@ -529,42 +543,54 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             } else {
                 load_frags(smem, 0, 0);
             }
-            if (kt_begin + 1 < kt_end) {
-                hot_advance(kt_begin + 1);
-                if (is_tail(kt_begin + 1)) {
-                    tail_tile(kt_begin + 1, smem + STAGE);
+            if (kt_begin + NS - 1 < kt_end) {
+                hot_advance(kt_begin + NS - 1);
+                if (is_tail(kt_begin + NS - 1)) {
+                    tail_tile(kt_begin + NS - 1, smem + (NS - 1) * STAGE);
                 } else {
-                    const uint32_t live = live_mask(kt_begin + 1);
+                    const uint32_t live = live_mask(kt_begin + NS - 1);
 #pragma unroll
-                    for (int n = 0; n < NL; ++n) hot_load(I0{}, n, smem + STAGE, live);
+                    for (int n = 0; n < NL; ++n) hot_load(I0{}, n, smem + (NS - 1) * STAGE, live);
                 }
             }
         }
-        uint32_t live1 = live_mask(kt_begin + 1);  // tile kt+1 at the top of iteration kt
+        uint32_t live1 = live_mask(kt_begin + NS - 1);  // tile kt+NS-1 at the top of iteration kt
+        // all ones while the tiles kt+2 .. kt+NS-1 all went out as direct loads (bit j: tile kt+2+j)
+        uint32_t later = 0;
+        if constexpr (NS > 2) {
+#pragma unroll
+            for (int j = 0; j < NS - 2; ++j) later |= (live_mask(kt_begin + 2 + j) & 1u) << j;
+        }
+        int si = 0;  // stage of tile kt
         for (int kt = kt_begin; kt < kt_end; ++kt) {
-            char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
-            char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
-            const uint32_t live2 = live_mask(kt + 2);
+            // (with two stages the same expressions as ever: the register allocation of the 256x256 kernels,
+            // which use every register, does not survive a change here)
+            char* cur = smem + (NS == 2 ? (kt - kt_begin) & 1 : si) * STAGE;
+            char* nxt = smem + (NS == 2 ? ((kt - kt_begin) & 1) ^ 1 : (si + 1 == NS ? 0 : si + 1)) * STAGE;  // tile kt+1
+            char* prv = NS == 2 ? nxt : smem + (si == 0 ? NS - 1 : si - 1) * STAGE;  // tile kt+NS-1 (the stage tile kt-1 left)
+            const uint32_t live2 = live_mask(kt + NS);
             using SH = std::integral_constant<int, NS2 / 2>;
             using SE = std::integral_constant<int, NS2>;
-            if constexpr (MF16) slots16(I0{}, I0{}, SE{}, std::true_type{}, I1{}, I1{}, cur, nxt, live1);
-            else kstep(I0{}, I1{}, I1{}, cur, nxt, live1);  // + second half of tile kt+1
-            if (kt + 2 < kt_end) hot_advance(kt + 2);
+            if constexpr (MF16) slots16(I0{}, I0{}, SE{}, std::true_type{}, I1{}, I1{}, cur, prv, live1);
+            else kstep(I0{}, I1{}, I1{}, cur, prv, live1);  // + second half of tile kt+NS-1
+            if (kt + NS < kt_end) hot_advance(kt + NS);
             if constexpr (MF16) {
                 slots16(I1{}, I0{}, SH{}, std::false_type{}, I0{}, NOLD{}, cur, nxt, 0);
             } else {
                 kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
                 kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
             }
-            wait_loads();
+            wait_loads(NS > 2 && later == (1u << (NS > 2 ? NS - 2 : 0)) - 1u);
             __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
-            if (live2 == 0) {        // no tile kt+2, or a tail tile (rare)
-                if (kt + 2 < kt_end) tail_tile(kt + 2, cur);
+            if (live2 == 0) {        // no tile kt+NS, or a tail tile (rare)
+                if (kt + NS < kt_end) tail_tile(kt + NS, cur);
             }
-            // + first half of tile kt+2 (harmless stale reads after the last tile)
+            // + first half of tile kt+NS (harmless stale reads after the last tile)
             if constexpr (MF16) slots16(I1{}, SH{}, SE{}, std::true_type{}, I0{}, I0{}, nxt, cur, live2);
             else kstep(I1{}, I0{}, I0{}, nxt, cur, live2);
+            if constexpr (NS > 2) later = (later >> 1) | ((live2 & 1u) << (NS - 3));
             live1 = live2;
+            if constexpr (NS > 2) si = si + 1 == NS ? 0 : si + 1;
         }
     }
     __syncthreads();  // LDS is free for the epilogue
@@ -818,10 +844,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     }
 }
 
-template <int BM, int BN, int EPI, bool ARC, bool BRC>
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC>;
-    constexpr int smem = NtCfg<BM, BN>::SMEM;
+    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS>;
+    constexpr int smem = NtCfg<BM, BN, NS>::SMEM;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -906,6 +932,15 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     }
     if (choice == 1) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
     if (choice == 2) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
+    if constexpr (EPI == EPI_F32_SPLITK) {
+        // The fp32 slices (dB and its relatives: short rows of 128 outputs, both operands stored K x rows) wait for
+        // their loads more than for anything else on 128x128 tiles with two stages.  A 256x128 tile leaves room
+        // for a third stage (144 KB), which puts a whole k-tile more in flight: dB 0.78 -> 0.66 ms on the 7B block.
+        // (Four stages of 128x128, or three of either shape for the merge, measured slower.)
+        // From 1024 output rows (rank 1024) up; at rank 512 (1B block) it measured equal or slightly behind.
+        if (g_nt_tile_override == 0 && p.M >= 1024)
+            return launch_nt<256, 128, EPI, ARC, BRC, 3>(p, st);
+    }
     return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
     }
 }

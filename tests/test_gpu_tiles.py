@@ -105,3 +105,28 @@ def test_forced_tiles_right_side(tile, T, out, inp, r):
     eb = G.max_err_over_rms(dBp.cpu().numpy().astype(np.float64), dB_ref)
     print(f"tile {tile} right T={T} out={out} in={inp} r={r}: err/rms y {ey:.2e} dx {ex:.2e} dBp {eb:.2e}")
     assert ey <= TOL and ex <= TOL and eb <= TOL
+
+
+@pytest.mark.parametrize("T", [70, 200, 1100])
+def test_rank_1024_gradient_uses_the_three_stage_tiles(T):
+    """From rank 1024 up the fp32 slices of dB run on 256x128 tiles with three LDS stages, whatever the other
+    sizes: contractions (over T) of two k-tiles (fewer than the stages), of four with a short last one, and of two
+    slices with a short last k-tile."""
+    from tests import gpu_util as G
+    from paper_2405_16528_amd import binding as L
+    out, inp, r, s = 1100, 200, 1024, 0.5
+    L.set_path(L.PATH_FOLDED)
+    try:
+        lay, Wq, Pq, d = _setup(T, out, inp, r, seed=T, sigma_B=2e-2)
+        dx = G.bf16_empty(T, inp, fill=float("nan"))
+        dB = torch.full((r, inp), float("nan"), dtype=torch.float32, device="cuda")
+        L.loqt_linear_bwd(d["dy"], d["x"], d["Wq"], d["Pq"], d["B"], s, dx, dB, False,
+                          G.workspace(L.OP_BWD, T, out, inp, r))
+        torch.cuda.synchronize()
+    finally:
+        L.set_path(L.PATH_AUTO)
+    dx_ref, dB_ref = O.loqt_linear_bwd(lay.dy, lay.x, Wq, Pq, lay.B, s)
+    ex = G.max_err_over_rms(O.bf16_to_f64(G.bf16_host(dx)), dx_ref)
+    eb = G.max_err_over_rms(dB.cpu().numpy().astype(np.float64), dB_ref)
+    print(f"r=1024 T={T}: err/rms dx {ex:.2e} dB {eb:.2e}")
+    assert ex <= TOL and eb <= TOL
