@@ -7,26 +7,30 @@
 // below) instead of once per output tile; at thousands of tokens that costs a few per cent of the
 // GEMM and keeps every VALU and LDS cycle of the inner loop for feeding the matrix cores.
 //
-// Work-group: 256 threads = 4 waves (2 x 2), tile BM x BN x 64, v_mfma_f32_32x32x16_bf16.
-//  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no
-//    registers, no ds_write); two LDS stages.  When every K segment is a whole number of k-tiles
-//    the loads of a tile are issued one by one between the MFMAs, half of them in the k16 step
-//    right after the barrier that frees the stage and half in the next one, so the matrix cores
-//    never wait for a burst of loads and every load has half a tile of MFMAs or more to land;
-//    the general loop (K tails) issues a tile's loads in one piece after that barrier;
-//  * 16-byte chunks of an LDS row are XOR-swizzled; the swizzle is applied on the global side
-//    (which chunk a lane fetches), the LDS side of a direct load is lane-linear;
+// Work-group: 256 threads = 4 waves (2 x 2), tile BM x BN x 64; v_mfma_f32_16x16x32_bf16 for the plain bf16
+// products on 256x256 tiles (most of a training step), v_mfma_f32_32x32x16_bf16 for everything else.
+//  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no registers, no
+//    ds_write) into a ring of NS stages (two; three for the fp32 slices of dB).  There is one loop for
+//    every case: the loads of a tile are issued one by one between the MFMAs, half of them after the
+//    barrier that frees the stage and half in the next k-step, so the matrix cores never wait for a burst
+//    of loads and every load has most of a tile of MFMAs to land; loads past the end of the range are
+//    switched off through EXEC, and a k-tile that is not full (the last one of a K segment that is not a
+//    multiple of 64) is staged through registers with zero fill instead;
+//  * 16-byte chunks of an LDS row are XOR-swizzled so that fragment reads are free of bank conflicts (the
+//    pattern depends on the MFMA shape); the swizzle is applied on the global side (which chunk a lane
+//    fetches), the LDS side of a direct load is lane-linear;
 //  * K-contiguous tiles are read back with one 16-byte read per fragment, row-contiguous tiles
 //    with two transposing reads (ds_read_b64_tr_b16): no operand is ever transposed in memory;
-//  * MFMA fragments are double-buffered in registers one k16 step ahead, reads interleaved
-//    one-to-one with the MFMAs of the running step (a scheduling fence after every MFMA slot
-//    in the whole-tile loop, sched_group_barrier in the general one);
+//  * MFMA fragments are double-buffered in registers one k-step ahead; the instruction order of the loop
+//    is fixed by hand (a scheduling fence after every MFMA slot): fragment reads after the first MFMAs of
+//    a step, direct loads after the last ones;
 //  * the accumulators are kept transposed (lane = row m, registers = 4 consecutive n) so the
 //    epilogues can pack along n: bf16 results are staged through LDS and leave as whole
 //    16-byte-per-lane row segments; the fold epilogue adds the dequantised NF4 weight on the way;
 //    the merge epilogue requantises 64-blocks in registers (paper sec. 5.1, Alg. 1 line 5);
 //  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in 8-row groups so that the
 //    work-groups sharing an L2 also share operand panels.
+// The 256x256 kernels use every vector register; tests/test_isa_guard.py checks their generated loop.
 #include <type_traits>
 
 #include "loqt_internal.h"
