@@ -398,6 +398,27 @@ def main():
     }
     if not args.no_extras:
         out["extras"] = extras(L, synth, torch, wl, full_precision, layers)
+        # the same step captured once as a HIP graph and replayed (the library allocates nothing and keeps no
+        # state, so the capture holds only its kernels): what the gaps between the launches of a step cost
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t6 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t7 = time.perf_counter()
+        out["extras"]["graph_replay"] = {"mode": args.mode, "ms_per_step": (t7 - t6) * 1e3 / args.steps,
+                                         "value": (f_fb + f_mg) / ((t7 - t6) / args.steps) / 1e12}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, args.seed, min(args.cpu_sample_tokens, T))
     print(json.dumps(out))
