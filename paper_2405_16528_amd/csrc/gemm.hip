@@ -406,6 +406,40 @@ __global__ __launch_bounds__(256) void reduce_db_kernel(const float* __restrict_
     }
 }
 
+// The same sum four columns per thread (16-byte loads and stores); N, ldp and ld_dB multiples of 4, pointers
+// aligned to match.  The order of the additions per element is the same as above.
+__global__ __launch_bounds__(256) void reduce_db4_kernel(const float* __restrict__ partials, int splits,
+                                                         int64_t M, int N4, int64_t ldp, void* __restrict__ dB,
+                                                         int dB_bf16, int64_t ld_dB, int accumulate) {
+    const int64_t total = M * N4;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * 256) {
+        const int64_t m = idx / N4;
+        const int n = (int)(idx - m * N4) * 4;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int k = 0; k < splits; ++k) {
+            const float4 v = *reinterpret_cast<const float4*>(partials + ((int64_t)k * M + m) * ldp + n);
+            s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+        }
+        if (dB_bf16) {
+            uint2* d = reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(dB) + m * ld_dB + n);
+            if (accumulate) {
+                const uint2 o = *d;
+                s.x += __uint_as_float(o.x << 16), s.y += __uint_as_float(o.x & 0xffff0000u);
+                s.z += __uint_as_float(o.y << 16), s.w += __uint_as_float(o.y & 0xffff0000u);
+            }
+            *d = make_uint2(pack_bf16(s.x, s.y), pack_bf16(s.z, s.w));
+        } else {
+            float4* d = reinterpret_cast<float4*>(reinterpret_cast<float*>(dB) + m * ld_dB + n);
+            if (accumulate) {
+                const float4 o = *d;
+                s.x += o.x, s.y += o.y, s.z += o.z, s.w += o.w;
+            }
+            *d = s;
+        }
+    }
+}
+
 template <int BM, int BN, int AK, int BK0, int BK1, int EPI>
 hipError_t launch_one(const GemmParams& p, hipStream_t st) {
     auto kern = loqt_gemm_kernel<BM, BN, AK, BK0, BK1, EPI>;
@@ -478,6 +512,15 @@ hipError_t launch_gemm(GemmId id, const GemmParams& p, hipStream_t st) {
 hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, int64_t ldp, void* dB,
                             int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st) {
     TimedLaunch tl(SLOT_REDUCE_DB, st);
+    const bool bf16 = dB_dtype == LOQT_BF16;
+    if (N % 4 == 0 && ldp % 4 == 0 && ld_dB % 4 == 0 && (reinterpret_cast<uintptr_t>(partials) & 15) == 0 &&
+        (reinterpret_cast<uintptr_t>(dB) & (bf16 ? 7 : 15)) == 0) {
+        int64_t blocks4 = (M * (N / 4) + 255) / 256;
+        if (blocks4 > 256 * 16) blocks4 = 256 * 16;
+        hipLaunchKernelGGL(reduce_db4_kernel, dim3((int)blocks4), dim3(256), 0, st, partials, splits, M, (int)(N / 4),
+                           ldp, dB, bf16 ? 1 : 0, ld_dB, accumulate);
+        return hipGetLastError();
+    }
     int64_t blocks = (M * N + 255) / 256;
     if (blocks > 256 * 32) blocks = 256 * 32;
     hipLaunchKernelGGL(reduce_db_kernel, dim3((int)blocks), dim3(256), 0, st, partials, splits, M, (int)N,
