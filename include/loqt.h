@@ -394,6 +394,15 @@ int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in);
  */
 enum { LOQT_TILE_AUTO = 0, LOQT_TILE_256x256 = 1, LOQT_TILE_256x128 = 2, LOQT_TILE_128x128 = 3 };
 loqt_status loqt_set_tile(int tile);
+/*
+ * Diagnostic (host only, no GPU work): how a bf16-output product of M rows and N columns (plus Nx extra
+ * columns that share the left operand, 0 if none) that is large enough for 256x256 tiles is laid out
+ * under LOQT_TILE_AUTO.  *n_large = 0: one launch of 256x256 tiles; otherwise the first *n_large columns
+ * (a multiple of 256, < N) go out as 256x256 tiles in whole rounds of 256 and the remaining columns, with
+ * the extra ones, as a second launch of 128x128 tiles.  *rounds = the estimated duration in rounds of
+ * 256x256 tiles.  Either pointer may be NULL.  Returns LOQT_BAD_SHAPE for M, N <= 0 or Nx < 0.
+ */
+loqt_status loqt_plan_product(int64_t M, int64_t N, int64_t Nx, int64_t *n_large, double *rounds);
 
 /*
  * Optional per-kernel timing (diagnostics for benchmarks; off by default).

@@ -103,6 +103,8 @@ lib.loqt_absmax_dq_expand.restype = _i
 lib.loqt_absmax_dq_expand.argtypes = [_vp, _vp, _vp, _i64, _vp, _vp]
 lib.loqt_set_path.restype = _i
 lib.loqt_set_path.argtypes = [_i]
+lib.loqt_plan_product.restype = _i
+lib.loqt_plan_product.argtypes = [_i64, _i64, _i64, _P(_i64), _P(C.c_double)]
 lib.loqt_set_tile.restype = _i
 lib.loqt_set_tile.argtypes = [_i]
 lib.loqt_resolved_path.restype = _i
@@ -378,6 +380,14 @@ def loqt_init_compensate(W: torch.Tensor, P: torch.Tensor, s: float, iters: int,
 def set_path(path: int) -> None:
     """PATH_AUTO, PATH_FUSED or PATH_PREPASS (process-wide)."""
     _check(lib.loqt_set_path(path), "loqt_set_path")
+
+
+def plan_product(M: int, N: int, Nx: int = 0):
+    """(columns that run on 256x256 tiles before a 128x128 tail launch, or 0; estimated rounds) -- host only."""
+    n = _i64(0)
+    c = C.c_double(0.0)
+    _check(lib.loqt_plan_product(M, N, Nx, C.byref(n), C.byref(c)), "loqt_plan_product")
+    return int(n.value), float(c.value)
 
 
 def set_tile(tile: int) -> None:

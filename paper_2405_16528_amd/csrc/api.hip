@@ -1186,6 +1186,15 @@ loqt_status loqt_set_tile(int tile) {
     return LOQT_OK;
 }
 
+loqt_status loqt_plan_product(int64_t M, int64_t N, int64_t Nx, int64_t* n_large, double* rounds) {
+    if (M <= 0 || N <= 0 || Nx < 0 || M > ((int64_t)1 << 30) || N > ((int64_t)1 << 30) || Nx > ((int64_t)1 << 30))
+        return LOQT_BAD_SHAPE;
+    const BF16Plan plan = plan_bf16_product(M, N, Nx);
+    if (n_large) *n_large = plan.n1;
+    if (rounds) *rounds = plan.cost;
+    return LOQT_OK;
+}
+
 void loqt_timing_enable(int on) {
     if (on) {
         if (!g_timing.begin) {

@@ -29,7 +29,7 @@ def test_every_declared_symbol_is_exported(lib):
             "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule",
             "loqt_absmax_dq_workspace_bytes", "loqt_absmax_dq_compress", "loqt_absmax_dq_expand",
             "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq", "loqt_linear_fwd_save",
-            "loqt_linear_bwd_saved", "loqt_set_tile"} <= names
+            "loqt_linear_bwd_saved", "loqt_set_tile", "loqt_plan_product"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
@@ -182,3 +182,35 @@ def test_merge_schedule_matches_the_oracle(lib):
     assert L.loqt_merge_schedule(5, tau=200.0, psi=1.0) == [201, 402, 603, 804, 1005]
     assert L.loqt_merge_schedule(200, tau=50.0, psi=1.5, cap=300) == O.merge_schedule(50, 1.5, 300, 200)
     assert L.loqt_merge_schedule(0) == []
+
+
+def test_product_plan_is_valid_and_never_worse_than_one_launch(lib):
+    """loqt_plan_product is host code.  Whatever the sizes: the 256x256 part is a whole number of tile columns
+    short of N, its tiles nearly fill whole rounds of 256, and the plan is never priced above the single launch."""
+    from paper_2405_16528_amd import binding as L
+
+    def cdiv(a, b):
+        return -(-a // b)
+
+    # the shapes the workloads produce (T, columns, extra columns)
+    assert L.plan_product(8192, 4096) == (0, 2.0)                  # two exact rounds
+    assert L.plan_product(8192, 11008)[0] == 10240                 # 5.4 rounds: 5 + a 128x128 tail
+    assert L.plan_product(8192, 11008, 1024) == (0, 6.0)           # Z rides along and fills the sixth round
+    assert L.plan_product(4096, 5120, 1024)[0] == 4096             # 1.25 rounds: 1 + tail that takes Z along
+    assert L.plan_product(4096, 5120)[0] == 4096
+    for M in (256, 1000, 4096, 8192, 12000):
+        for N in (256, 2048, 4096, 5120, 5461, 11008, 13824):
+            for Nx in (0, 512, 1024):
+                n1, cost = L.plan_product(M, N, Nx)
+                one = cdiv(cdiv(M, 256) * (cdiv(N, 256) + cdiv(Nx, 256)), 256)
+                assert cost <= one
+                if n1:
+                    assert n1 % 256 == 0 and 0 < n1 < N
+                    tiles_a = cdiv(M, 256) * (n1 // 256)
+                    assert tiles_a <= (tiles_a // 256 + 1) * 256 and 256 * cdiv(tiles_a, 256) - tiles_a < 32
+                    assert cost < one
+                else:
+                    assert cost == one
+    assert lib.loqt_plan_product(0, 4096, 0, None, None) == 2
+    assert lib.loqt_plan_product(4096, 4096, -1, None, None) == 2
+    assert lib.loqt_plan_product(4096, 4096, 0, None, None) == 0
