@@ -72,7 +72,7 @@ def _requant_policy_check(c, a, W, P, B0, s):
     out, inp = c_ref.shape
     nblk = a_ref.shape[1]
     r = Pd.shape[1]
-    E = abs(s) * (np.abs(Pd) @ np.abs(B0)) * (2.0 ** -9 + (r + 2) * 2.0 ** -24) + np.abs(What) * 2.0 ** -22
+    E = abs(s) * (np.abs(Pd) @ np.abs(B0)) * (2.0 ** -8 + (r + 2) * 2.0 ** -24) + np.abs(What) * 2.0 ** -22
     Emax = np.pad(E, ((0, 0), (0, nblk * 64 - inp))).reshape(out, nblk, 64).max(axis=2)
     a64 = a_ref.astype(np.float64)
     assert np.all(np.abs(a.astype(np.float64) - a64) <= Emax + 1e-30), "absmax outside the error bound"

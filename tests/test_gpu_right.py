@@ -84,7 +84,7 @@ def _merge_policy_check(c, a, Wq, Qq, Bp, s):
     nblk = a_ref.shape[1]
     Qd = np.abs(O.nf4_dequantize_f64(*Qq))
     r = Qd.shape[1]
-    E = abs(s) * (np.abs(O.bf16_to_f64(Bp)) @ Qd.T) * (2.0 ** -9 + (r + 2) * 2.0 ** -24) + np.abs(Wm) * 2.0 ** -22
+    E = abs(s) * (np.abs(O.bf16_to_f64(Bp)) @ Qd.T) * (2.0 ** -8 + (r + 2) * 2.0 ** -24) + np.abs(Wm) * 2.0 ** -22
     Emax = np.pad(E, ((0, 0), (0, nblk * 64 - inp))).reshape(out, nblk, 64).max(axis=2)
     a64 = a_ref.astype(np.float64)
     assert np.all(np.abs(a.astype(np.float64) - a64) <= Emax + 1e-30), "absmax outside the error bound"
