@@ -611,19 +611,45 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         }
         char* ebuf = smem + wave * (WTM * EPITCH);
         const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
+        // A block of rows is staged through the wave's private LDS region and leaves as whole 16-byte row
+        // segments right after it has been computed (LDS operations of one wave complete in order, so no
+        // barrier), so that the stores of one block are under way while the next one is computed.
+        constexpr int CPR = WTN / 8;  // 16-byte chunks per row
+        uint16_t* C = reinterpret_cast<uint16_t*>(part1 ? p.Cx : p.C);
+        const int64_t ldc = part1 ? p.ldcx : p.ldc;
+        auto store_rows = [&](int row0, int nrows) {  // rows row0 .. row0+nrows-1 of the wave tile
+#pragma unroll 4
+            for (int it = 0; it < nrows * CPR / 64; ++it) {
+                const int idx = it * 64 + lane, row = row0 + idx / CPR, ch = idx % CPR;
+                const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + ch * 8;
+                const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * EPITCH + ch * 16);
+                if (m < p.M) {
+                    uint16_t* dst = C + (int64_t)m * ldc + n;
+                    if (n + 8 <= N) {
+                        *reinterpret_cast<uint4*>(dst) = v;
+                    } else {
+                        const uint16_t* sv = reinterpret_cast<const uint16_t*>(&v);
+                        for (int e = 0; e < 8; ++e)
+                            if (n + e < N) dst[e] = sv[e];
+                    }
+                }
+            }
+        };
         if constexpr (MF16) {
             const int frow16 = lane & 15, q4 = lane >> 4;
 #pragma unroll
-            for (int ti = 0; ti < TM2; ++ti)
+            for (int ti = 0; ti < TM2; ++ti) {
 #pragma unroll
                 for (int tj = 0; tj < TN2; ++tj) {
                     const uint2 v = make_uint2(pack_bf16(alpha * acc16[ti][tj][0], alpha * acc16[ti][tj][1]),
                                                pack_bf16(alpha * acc16[ti][tj][2], alpha * acc16[ti][tj][3]));
                     *reinterpret_cast<uint2*>(ebuf + (ti * 16 + frow16) * EPITCH + (tj * 16 + 4 * q4) * 2) = v;
                 }
+                if (ti & 1) store_rows((ti - 1) * 16, 32);
+            }
         } else {
 #pragma unroll
-        for (int ti = 0; ti < TM; ++ti)
+        for (int ti = 0; ti < TM; ++ti) {
 #pragma unroll
             for (int tj = 0; tj < TN; ++tj) {
                 // folded weight (M = out, N = in): the 16 code bytes of row m, columns nt..nt+31 (both
@@ -664,26 +690,8 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                     *reinterpret_cast<uint2*>(ebuf + (ti * 32 + frow) * EPITCH + (tj * 32 + 8 * g + 4 * h) * 2) = v;
                 }
             }
+            store_rows(ti * 32, 32);
         }
-        // the region is private to the wave and LDS operations of one wave complete in order
-        constexpr int CPR = WTN / 8;  // 16-byte chunks per row
-        uint16_t* C = reinterpret_cast<uint16_t*>(part1 ? p.Cx : p.C);
-        const int64_t ldc = part1 ? p.ldcx : p.ldc;
-#pragma unroll 4
-        for (int it = 0; it < WTM * CPR / 64; ++it) {
-            const int idx = it * 64 + lane, row = idx / CPR, ch = idx % CPR;
-            const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + ch * 8;
-            const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * EPITCH + ch * 16);
-            if (m < p.M) {
-                uint16_t* dst = C + (int64_t)m * ldc + n;
-                if (n + 8 <= N) {
-                    *reinterpret_cast<uint4*>(dst) = v;
-                } else {
-                    const uint16_t* s = reinterpret_cast<const uint16_t*>(&v);
-                    for (int e = 0; e < 8; ++e)
-                        if (n + e < N) dst[e] = s[e];
-                }
-            }
         }
     } else if (EPI == EPI_F32_SPLITK || EPI == EPI_FOLD_F32) {
         // fp32 results, 16 bytes per lane (row m, 4 consecutive n).  EPI_F32_SPLITK: slice blockIdx.y of the
