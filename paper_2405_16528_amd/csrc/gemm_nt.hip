@@ -626,7 +626,8 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 if (m < p.M) {
                     uint16_t* dst = C + (int64_t)m * ldc + n;
                     if (n + 8 <= N) {
-                        *reinterpret_cast<uint4*>(dst) = v;
+                        typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+                        __builtin_nontemporal_store(__builtin_bit_cast(u32x4_t, v), reinterpret_cast<u32x4_t*>(dst));
                     } else {
                         const uint16_t* sv = reinterpret_cast<const uint16_t*>(&v);
                         for (int e = 0; e < 8; ++e)
