@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 METRIC = "LoQT NF4 linear fwd+bwd TFLOP/s at 7B shapes; merge+requant GB/s"
 
 # HBM-side traffic of the dominant kernel per launch, from profiles/bench_7b_block_hbm_traffic.md
-# per gemm_y launch slot: 256x256 kernel fetch 675.1 MB + write 98.1 MB, plus 2/7 of the 128x128 tail
+# per gemm_y launch slot: 256x256 kernel fetch 674.9 MB + write 98.3 MB, plus 2/7 of the 128x128 tail
 # launch of the gate and up projections (117.6 + 12.6 MB); null for workloads that were not profiled.
 TRAFFIC_BYTES_PER_LAUNCH = {"7b_block": 810.4e6}
 
