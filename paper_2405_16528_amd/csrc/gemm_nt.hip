@@ -81,13 +81,13 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     const int wm = wave >> 1, wn = wave & 1;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
 
-    // ---- tile of this work-group: contiguous range per XCD, 8-row groups inside
+    // ---- tile of this work-group: contiguous range per XCD, groups of GM tile rows inside
     const int tiles_m = (p.M + BM - 1) / BM;
     const int tiles_n0 = (p.N + BN - 1) / BN, tiles_n = tiles_n0 + (p.Nx + BN - 1) / BN;
     const int per_xcd = gridDim.x >> 3;
     const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (L >= tiles_m * tiles_n) return;
-    constexpr int GM = 8;
+    constexpr int GM = (EPI == EPI_BF16 && !ARC && !BRC) ? 4 : 8;  // measured per operand layout
     const int gid = L / (GM * tiles_n);
     const int first_m = gid * GM;
     const int gsz = min(tiles_m - first_m, GM);
