@@ -458,18 +458,20 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 else fb16[nb][j] = *reinterpret_cast<const bf16x8*>(stage + b_ko[ks] + j * 16 * ROWB);
             }
         };
-        // slots S0..S1-1 (two MFMAs each) of a k32 step on fragment buffer CB.  RD: fragment reads of k32 step RKS of
-        // the tile at `rstage` into the other buffer, spread over the first slots of the range.  LD (0 / 1, or -1):
-        // the loads of that half of the tile at hotA / hotB into `lstage`, one per slot on the last slots.
+        // slots S0..S1-1 (two MFMAs each) of a k32 step on fragment buffer CB.  RD > 0: the fragment reads of k32 step
+        // RKS of the tile at `rstage` into the other buffer, RD per slot from the first slot of the range on.  LD (0 / 1:
+        // that half of the tile at hotA / hotB, 2: all of it, -1: none): its loads into `lstage`, one per slot on the
+        // last slots of the range.
+        using I2tag = std::integral_constant<int, 2>;
         auto slots16 = [&](auto cb_tag, auto s0_tag, auto s1_tag, auto rd_tag, auto rks_tag, auto ld_tag, const char* rstage,
                            char* lstage, uint32_t live) {
             constexpr int CB = decltype(cb_tag)::value, S0 = decltype(s0_tag)::value, S1 = decltype(s1_tag)::value;
-            constexpr bool RD = decltype(rd_tag)::value;
+            constexpr int RPS = decltype(rd_tag)::value;                 // fragment reads per slot
             constexpr int RKS = decltype(rks_tag)::value, LD = decltype(ld_tag)::value;
             constexpr int NSL = S1 - S0;
-            constexpr int RPS = (NU2 + NSL - 1) / NSL;                   // fragment reads per slot
-            constexpr int LPS16 = (NL + NSL - 1) / NSL;                  // loads per slot ...
-            constexpr int LSL = (NL + LPS16 - 1) / LPS16;                // ... on LSL slots ...
+            constexpr int NLD = LD == 2 ? Cfg::NCH : NL;                 // loads to place ...
+            constexpr int LPS16 = (NLD + NSL - 1) / NSL;                 // ... LPS16 per slot ...
+            constexpr int LSL = (NLD + LPS16 - 1) / LPS16;               // ... on LSL slots ...
             constexpr int LST = NSL >= 2 * LSL ? 2 : 1;                  // ... every LST-th of the last LST * LSL
 #pragma unroll
             for (int sl = S0; sl < S1; ++sl) {
@@ -479,15 +481,21 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                     acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb16[CB][j], fa16[CB][i], acc16[i][j], 0, 0, 0);
                 }
                 const int t = sl - S0;
-                if constexpr (RD) {
+                if constexpr (RPS > 0) {
 #pragma unroll
                     for (int u = t * RPS; u < (t + 1) * RPS && u < NU2; ++u) rd16(RKS, CB ^ 1, u, rstage);
                 }
-                if constexpr (LD >= 0) {
+                if constexpr (LD >= 10) {
+                    // spread form: the whole tile, one load every third slot from slot LD - 10 of the schedule on
+                    // (this range starts at schedule slot LD - 10)
+                    constexpr int LSPREAD = 3;
+                    const int g = LD - 10 + t;
+                    if (g % LSPREAD == 0 && g / LSPREAD < Cfg::NCH) hot_load(I2tag{}, g / LSPREAD, lstage, live);
+                } else if constexpr (LD >= 0) {
                     const int tl = t - (NSL - LST * LSL);
                     if (tl >= 0 && tl % LST == 0) {
 #pragma unroll
-                        for (int n = (tl / LST) * LPS16; n < (tl / LST + 1) * LPS16 && n < NL; ++n)
+                        for (int n = (tl / LST) * LPS16; n < (tl / LST + 1) * LPS16 && n < NLD; ++n)
                             hot_load(ld_tag, n, lstage, live);
                     }
                 }
@@ -524,6 +532,71 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             if (NS > 2 && later_live) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * Cfg::NCH) : "memory");
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         };
+        if constexpr (MF16) {
+            // ---- 16x16x32 form (two stages).  A stage is free as soon as the fragments of its second k32 step sit in
+            // registers, a quarter of the way into its tile, so its refill does not have to wait for the barrier
+            // that publishes the next tile.  Per k-tile kt:
+            //   slots  0-15 of k32 step 0: the fragment reads of step 1 (two per slot on the first eight)
+            //   barrier X                : every wave has tile kt in registers, its stage is free
+            //   slots 16-31 of step 0    : the 16 loads of tile kt+2 into that stage, one per slot
+            //   slots  0-15 of step 1    : MFMAs only
+            //   barrier Y                : tile kt+1 has landed (loads return in order: all but the 16 of kt+2)
+            //   slots 16-31 of step 1    : the fragment reads of step 0 of tile kt+1, one per slot
+            // A load so has from slot 16 of its issue tile to barrier Y of the next one, 1.25 to 1.5 k-tiles (about
+            // 3000 cycles), to land: measured against a library GEMM of the same tile shape, instruction mix and
+            // cache traffic, the loop with one barrier per tile (loads issued 0.25 to 1 tile ahead) spent 27 % of
+            // its wave cycles waiting where that kernel spent 6 %.
+            using SH = std::integral_constant<int, NS2 / 2>;
+            using SE = std::integral_constant<int, NS2>;
+            auto whole_tile = [&](int t, char* stage) -> bool {  // all of tile t into `stage`; true if by direct loads
+                if (is_tail(t)) {
+                    tail_tile(t, stage);
+                    return false;
+                }
+                const uint32_t live = live_mask(t);
+#pragma unroll
+                for (int n = 0; n < Cfg::NCH; ++n) hot_load(I2{}, n, stage, live);
+                return true;
+            };
+            if (kt_begin < kt_end) {
+                hot_setup(kt_begin);
+                whole_tile(kt_begin, smem);
+                bool second = false;
+                if (kt_begin + 1 < kt_end) {
+                    hot_advance(kt_begin + 1);
+                    second = whole_tile(kt_begin + 1, smem + STAGE);
+                }
+                if (second) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(Cfg::NCH) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < NU2; ++u) rd16(0, 0, u, smem);
+            }
+            for (int kt = kt_begin; kt < kt_end; ++kt) {
+                char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
+                char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
+                const uint32_t live2 = live_mask(kt + 2);
+                slots16(I0{}, I0{}, SH{}, I2{}, I1{}, NOLD{}, cur, cur, 0);
+                __syncthreads();  // X: nobody reads `cur` any more
+                if (kt + 2 < kt_end) {
+                    hot_advance(kt + 2);
+                    if (live2 == 0) tail_tile(kt + 2, cur);  // a tail tile (rare): through registers
+                }
+                // the 16 loads of tile kt+2 go out one every third slot over the remaining 48 slots of the tile: the
+                // memory pipeline limits the requests in flight per compute unit, and a burst of loads stalls the
+                // issue of the MFMAs behind it
+                slots16(I0{}, SH{}, SE{}, I0{}, I0{}, std::integral_constant<int, 10>{}, cur, cur, live2);
+                slots16(I1{}, I0{}, SH{}, I0{}, I0{}, std::integral_constant<int, 10 + NS2 / 2>{}, cur, cur, live2);
+                // tile kt+1 must have landed; the loads of tile kt+2 issued so far (schedule slots 0-31: 11 of them)
+                // came after it and may stay in flight, provided they went out as direct loads (a masked load may
+                // not count)
+                if (live2 != 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS2 - 1) / 3 + 1) : "memory");
+                else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();  // Y
+                // harmless stale reads after the last tile
+                slots16(I1{}, SH{}, SE{}, I1{}, I0{}, std::integral_constant<int, 10 + NS2>{}, nxt, cur, live2);
+            }
+        } else {
         if (kt_begin < kt_end) {
             hot_setup(kt_begin);
 #pragma unroll
@@ -541,12 +614,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             }
             wait_loads(false);
             __syncthreads();
-            if constexpr (MF16) {
-#pragma unroll
-                for (int u = 0; u < NU2; ++u) rd16(0, 0, u, smem);
-            } else {
-                load_frags(smem, 0, 0);
-            }
+            load_frags(smem, 0, 0);
             if (kt_begin + NS - 1 < kt_end) {
                 hot_advance(kt_begin + NS - 1);
                 if (is_tail(kt_begin + NS - 1)) {
@@ -573,30 +641,23 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
             char* nxt = smem + (NS == 2 ? ((kt - kt_begin) & 1) ^ 1 : (si + 1 == NS ? 0 : si + 1)) * STAGE;  // tile kt+1
             char* prv = NS == 2 ? nxt : smem + (si == 0 ? NS - 1 : si - 1) * STAGE;  // tile kt+NS-1 (the stage tile kt-1 left)
             const uint32_t live2 = live_mask(kt + NS);
-            using SH = std::integral_constant<int, NS2 / 2>;
-            using SE = std::integral_constant<int, NS2>;
-            if constexpr (MF16) slots16(I0{}, I0{}, SE{}, std::true_type{}, I1{}, I1{}, cur, prv, live1);
-            else kstep(I0{}, I1{}, I1{}, cur, prv, live1);  // + second half of tile kt+NS-1
+            kstep(I0{}, I1{}, I1{}, cur, prv, live1);  // + second half of tile kt+NS-1
             if (kt + NS < kt_end) hot_advance(kt + NS);
-            if constexpr (MF16) {
-                slots16(I1{}, I0{}, SH{}, std::false_type{}, I0{}, NOLD{}, cur, nxt, 0);
-            } else {
-                kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
-                kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
-            }
+            kstep(I1{}, I2{}, NOLD{}, cur, nxt, 0);
+            kstep(I0{}, I3{}, NOLD{}, cur, nxt, 0);
             wait_loads(NS > 2 && later == (1u << (NS > 2 ? NS - 2 : 0)) - 1u);
             __syncthreads();         // tile kt+1 has landed; nobody reads `cur` any more
             if (live2 == 0) {        // no tile kt+NS, or a tail tile (rare)
                 if (kt + NS < kt_end) tail_tile(kt + NS, cur);
             }
             // + first half of tile kt+NS (harmless stale reads after the last tile)
-            if constexpr (MF16) slots16(I1{}, SH{}, SE{}, std::true_type{}, I0{}, I0{}, nxt, cur, live2);
-            else kstep(I1{}, I0{}, I0{}, nxt, cur, live2);
+            kstep(I1{}, I0{}, I0{}, nxt, cur, live2);
             if constexpr (NS > 2) later = (later >> 1) | ((live2 & 1u) << (NS - 3));
             live1 = live2;
             if constexpr (NS > 2) si = si + 1 == NS ? 0 : si + 1;
         }
     }
+        }
     __syncthreads();  // LDS is free for the epilogue
 
     // ------------------------------------------------------------------ epilogues
