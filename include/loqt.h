@@ -60,7 +60,8 @@ enum {
     LOQT_BAD_SHAPE = 2,           /* pitch rule violated, operand shapes inconsistent, size 0 */
     LOQT_MISALIGNED = 3,          /* base pointer alignment rule violated */
     LOQT_WORKSPACE_TOO_SMALL = 4, /* ws_bytes < loqt_workspace_bytes(...) */
-    LOQT_LAUNCH_FAILED = 5        /* HIP reported an error at launch */
+    LOQT_LAUNCH_FAILED = 5,       /* HIP reported an error at launch */
+    LOQT_STATIC_SCRATCH_TOO_SMALL = 6 /* an allocation-free entry point was given more than its fixed scratch holds */
 };
 
 typedef uint16_t loqt_bf16; /* raw bfloat16 bits */
@@ -329,6 +330,21 @@ loqt_status loqt_absmax_dq_compress(const float *absmax, int64_t n, uint8_t *cod
                                     void *ws, size_t ws_bytes, void *hip_stream);
 loqt_status loqt_absmax_dq_expand(const uint8_t *codes8, const float *c1, const float *mean, int64_t n,
                                   float *absmax_out, void *hip_stream);
+
+/*
+ * loqt_absmax_dq_compress_static -- loqt_absmax_dq_compress for callers that cannot allocate device
+ * memory or bring a workspace: code recorded under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments without `ws`, same kernels, same bits in codes8, c1 and mean.  The
+ * partial sums of the mean go to a fixed 64 KB array inside the library's device image (one copy per GPU,
+ * held until the process ends), which bounds the call at loqt_absmax_dq_static_max_n() = 2^25 scales
+ * (2^31 weights); a larger n returns LOQT_STATIC_SCRATCH_TOO_SMALL and launches nothing.  The call
+ * allocates and frees nothing and records no memset.  The array's device address is looked up on the
+ * first call on each GPU (with the calling thread's current device, which must be the stream's).  All calls on
+ * one GPU share the array: they must be ordered (one stream, or events); calls that overlap on one GPU race.
+ */
+int64_t loqt_absmax_dq_static_max_n(void);
+loqt_status loqt_absmax_dq_compress_static(const float *absmax, int64_t n, uint8_t *codes8, float *c1,
+                                           float *mean, void *hip_stream);
 
 /*
  * loqt_adam_step -- the update between merges (Alg. 1 line 9: B_{t+1} = B_t - rho(G^B_t), rho = Adam;

@@ -27,7 +27,7 @@ OP_FWD_NQ, OP_BWD_NQ = 7, 8
 PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
 TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128 = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",
-                4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED"}
+                4: "LOQT_WORKSPACE_TOO_SMALL", 5: "LOQT_LAUNCH_FAILED", 6: "LOQT_STATIC_SCRATCH_TOO_SMALL"}
 
 
 class LoqtError(RuntimeError):
@@ -99,6 +99,10 @@ lib.loqt_absmax_dq_workspace_bytes.restype = _sz
 lib.loqt_absmax_dq_workspace_bytes.argtypes = [_i64]
 lib.loqt_absmax_dq_compress.restype = _i
 lib.loqt_absmax_dq_compress.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp, _sz, _vp]
+lib.loqt_absmax_dq_static_max_n.restype = _i64
+lib.loqt_absmax_dq_static_max_n.argtypes = []
+lib.loqt_absmax_dq_compress_static.restype = _i
+lib.loqt_absmax_dq_compress_static.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp]
 lib.loqt_absmax_dq_expand.restype = _i
 lib.loqt_absmax_dq_expand.argtypes = [_vp, _vp, _vp, _i64, _vp, _vp]
 lib.loqt_set_path.restype = _i
@@ -342,6 +346,15 @@ def loqt_absmax_dq_compress(absmax: torch.Tensor):
     _check(lib.loqt_absmax_dq_compress(a.data_ptr(), n, codes.data_ptr(), c1.data_ptr(), mean.data_ptr(),
                                        *_ws_args(ws), _stream()), "loqt_absmax_dq_compress")
     return codes, c1, mean
+
+
+def loqt_absmax_dq_compress_static(absmax: torch.Tensor, codes: torch.Tensor, c1: torch.Tensor,
+                                   mean: torch.Tensor) -> None:
+    """The allocation-free variant: every output is the caller's (codes uint8 [n], c1 float32 [ceil(n/256)],
+    mean float32 [1]); nothing is allocated here or in the library."""
+    a = absmax.reshape(-1)
+    _check(lib.loqt_absmax_dq_compress_static(a.data_ptr(), a.numel(), codes.data_ptr(), c1.data_ptr(),
+                                              mean.data_ptr(), _stream()), "loqt_absmax_dq_compress_static")
 
 
 def loqt_absmax_dq_expand(codes: torch.Tensor, c1: torch.Tensor, mean: torch.Tensor,

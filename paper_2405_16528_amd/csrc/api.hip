@@ -359,6 +359,7 @@ const char* loqt_status_string(loqt_status st) {
         case LOQT_MISALIGNED: return "LOQT_MISALIGNED";
         case LOQT_WORKSPACE_TOO_SMALL: return "LOQT_WORKSPACE_TOO_SMALL";
         case LOQT_LAUNCH_FAILED: return "LOQT_LAUNCH_FAILED";
+        case LOQT_STATIC_SCRATCH_TOO_SMALL: return "LOQT_STATIC_SCRATCH_TOO_SMALL";
     }
     return "LOQT_UNKNOWN_STATUS";
 }
@@ -1162,6 +1163,18 @@ loqt_status loqt_absmax_dq_compress(const float* absmax, int64_t n, uint8_t* cod
     LOQT_TRY(check_ws(ws, ws_bytes, loqt_absmax_dq_workspace_bytes(n)));
     if (!aligned(ws, 8)) return LOQT_MISALIGNED;
     LOQT_HIP(launch_dq_compress(absmax, n, codes8, c1, mean, reinterpret_cast<double*>(ws), (hipStream_t)hip_stream));
+    return LOQT_OK;
+}
+
+int64_t loqt_absmax_dq_static_max_n(void) { return dq_static_max_n(); }
+
+loqt_status loqt_absmax_dq_compress_static(const float* absmax, int64_t n, uint8_t* codes8, float* c1, float* mean,
+                                           void* hip_stream) {
+    if (!absmax || !codes8 || !c1 || !mean) return LOQT_INVALID_ARG;
+    if (n <= 0) return LOQT_BAD_SHAPE;
+    if (n > dq_static_max_n()) return LOQT_STATIC_SCRATCH_TOO_SMALL;
+    if (!aligned(absmax, 4) || !aligned(c1, 4) || !aligned(mean, 4)) return LOQT_MISALIGNED;
+    LOQT_HIP(launch_dq_compress_static(absmax, n, codes8, c1, mean, (hipStream_t)hip_stream));
     return LOQT_OK;
 }
 

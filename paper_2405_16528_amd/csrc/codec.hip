@@ -1,6 +1,8 @@
 // NF4 block codec kernels (paper sec. 5.1): stand-alone quantise and dequantise.
 // Both are pure HBM streams: 4 + 0.5625 bytes per element for the encoder,
 // 0.5625 + 2 (bf16) or 4 (fp32) for the decoder.
+#include <mutex>
+
 #include "loqt_internal.h"
 
 namespace loqt {
@@ -276,6 +278,54 @@ hipError_t launch_dq_expand(const uint8_t* codes, const float* c1, const float* 
     return hipGetLastError();
 }
 int64_t dq_partials(int64_t n) { return (n + DQ_CHUNK - 1) / DQ_CHUNK; }
+
+// ---------------------------------------------------------------------------------------
+// The same compression for callers that cannot allocate (HIP graph capture, serving loops): the
+// partial sums of the mean live in a file-scope device array instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy of the array at its own address, so the device
+// address is looked up once per device (with that device current) and kept; host code never uses
+// the array's name for anything else.  All calls on one GPU share the array: calls that overlap on
+// one GPU (two streams, two threads) race on it.  Nothing in it has to start at zero: each call
+// writes every partial sum it later reads.
+// ---------------------------------------------------------------------------------------
+constexpr int64_t DQ_STATIC_MAX_N = (int64_t)1 << 25;  // 2^25 scales = 2^31 weights per call
+constexpr size_t DQ_STATIC_BYTES = (size_t)(DQ_STATIC_MAX_N / DQ_CHUNK) * sizeof(double);  // 64 KB
+static __device__ __align__(256) unsigned char scratch[DQ_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+int64_t dq_static_max_n() { return DQ_STATIC_MAX_N; }
+
+// device address of `scratch` on the current device (resolved on first use, then cached)
+hipError_t dq_static_scratch(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_dq_compress_static(const float* absmax, int64_t n, uint8_t* codes, float* c1, float* mean,
+                                     hipStream_t st) {
+    if (n > DQ_STATIC_MAX_N) return hipErrorInvalidValue;  // the caller checks first; never launch past the array
+    void* ptr = nullptr;
+    hipError_t e = dq_static_scratch(&ptr);
+    if (e != hipSuccess) return e;
+    return launch_dq_compress(absmax, n, codes, c1, mean, reinterpret_cast<double*>(ptr), st);
+}
 
 hipError_t launch_quantize(const float* w, int64_t rows, int64_t cols, int64_t ld_w, uint8_t* codes,
                            float* absmax, int64_t ld_q, hipStream_t st) {

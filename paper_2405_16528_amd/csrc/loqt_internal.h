@@ -165,6 +165,12 @@ hipError_t launch_dq_compress(const float* absmax, int64_t n, uint8_t* codes, fl
 hipError_t launch_dq_expand(const uint8_t* codes, const float* c1, const float* mean, int64_t n, float* out,
                             hipStream_t st);
 int64_t dq_partials(int64_t n);
+// allocation-free variant: the partial sums live in a file-scope device array of codec.hip (at most
+// dq_static_max_n() scales per call); dq_static_scratch resolves and caches its address on the current device
+hipError_t launch_dq_compress_static(const float* absmax, int64_t n, uint8_t* codes, float* c1, float* mean,
+                                     hipStream_t st);
+hipError_t dq_static_scratch(void** out);
+int64_t dq_static_max_n();
 
 // operand storage kinds of the GEMM
 enum OpKind {

@@ -214,3 +214,15 @@ def test_product_plan_is_valid_and_never_worse_than_one_launch(lib):
     assert lib.loqt_plan_product(0, 4096, 0, None, None) == 2
     assert lib.loqt_plan_product(4096, 4096, -1, None, None) == 2
     assert lib.loqt_plan_product(4096, 4096, 0, None, None) == 0
+
+
+def test_static_entry_point_checks_before_any_gpu_call(lib):
+    """loqt_absmax_dq_compress_static refuses, on the host, a size beyond its fixed scratch (and the usual misuse)."""
+    P = 0x10000
+    limit = lib.loqt_absmax_dq_static_max_n()
+    assert limit == 1 << 25
+    assert lib.loqt_absmax_dq_compress_static(P, limit + 1, P, P, P, None) == 6
+    assert lib.loqt_status_string(6) == b"LOQT_STATIC_SCRATCH_TOO_SMALL"
+    assert lib.loqt_absmax_dq_compress_static(P, 0, P, P, P, None) == 2
+    assert lib.loqt_absmax_dq_compress_static(None, 16, P, P, P, None) == 1
+    assert lib.loqt_absmax_dq_compress_static(P + 2, 16, P, P, P, None) == 3
