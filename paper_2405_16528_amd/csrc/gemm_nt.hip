@@ -377,6 +377,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
                 :
                 : "v"(o), "s"(base), "s"(dst), "s"(live)
                 : "memory");
+            // M0 cannot be named as a clobber (the compiler reserves it and warns that a clobber is not honoured): it
+            // never keeps a value in M0 across other code, it writes M0 right in front of each of its own uses.
+            // tests/test_isa_guard.py checks that nothing else in the loop touches M0.  EXEC is restored to all
+            // ones, the value it has in this uniform control flow.
         };
         // fragment u (A fragments first) of k16 step ks of the tile at `stage` into buffer nb
         auto read_unit = [&](int ks, int nb, int u, const char* stage) {
@@ -404,11 +408,10 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
 #pragma unroll
                 for (int u = q * UPS; u < (q + 1) * UPS && u < NU; ++u) read_unit(KS, CB ^ 1, u, fstage);
                 if constexpr (LD >= 0) {
-                    if (q >= NM - NSL) {
+                    // the NL loads of the half spread evenly over the NM slots of the step (a burst of loads fills the
+                    // memory pipeline's queue and stalls the issue of the MFMAs behind it)
 #pragma unroll
-                        for (int n = (q - (NM - NSL)) * LPS; n < (q - (NM - NSL) + 1) * LPS; ++n)
-                            hot_load(ld_tag, n, lstage, live);
-                    }
+                    for (int n = q * NL / NM; n < (q + 1) * NL / NM; ++n) hot_load(ld_tag, n, lstage, live);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }

@@ -62,3 +62,11 @@ def test_main_loop_has_no_register_file_traffic(assembly, name):
     # the k-tile's memory instructions: 32 fragment reads (twice as many when B is read transposed) and 16 loads
     n_loads = sum("global_load_lds_dwordx4" in x for x in text)
     assert n_loads == 16, f"{name}: {n_loads} direct loads in the loop blocks, expected 16"
+    # M0 is written by the hand-written load sequence only (it cannot be declared as a clobber): every write of M0 in
+    # the loop is the s_mov of that sequence, directly followed by the EXEC set-up and the load it serves
+    for i, x in enumerate(text):
+        if re.search(r"\bm0\b", x) and "s_mov_b32 m0" not in x:
+            raise AssertionError(f"{name}: M0 used outside the direct-load sequence: {x.strip()}")
+        if "s_mov_b32 m0" in x:
+            nxt = [y.strip() for y in text[i + 1:i + 4]]
+            assert nxt[0].startswith("s_mov_b32 exec_lo") and nxt[2].startswith("global_load_lds_dwordx4"), (name, nxt)
