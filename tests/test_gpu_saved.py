@@ -51,7 +51,8 @@ def test_saved_pair_parity(T, out, inp, r, ldw, s):
     ey = G.max_err_over_rms(O.bf16_to_f64(G.bf16_host(y)), y_ref)
     ex = G.max_err_over_rms(O.bf16_to_f64(G.bf16_host(dx)), dx_ref)
     eb = G.max_err_over_rms(dB.cpu().numpy().astype(np.float64), dB_ref)
-    ew = G.max_err_over_rms(O.bf16_to_f64(G.bf16_host(w_eff)), W_ref)
+    # W_eff element by element: half a bf16 step of the result + the worst case of the bf16-operand product
+    ew = G.weff_check(G.bf16_host(w_eff), Wq, Pq, lay.B, s)
     print(f"T={T} out={out} in={inp} r={r} s={s}: err/rms y {ey:.2e} dx {ex:.2e} dB {eb:.2e} W_eff {ew:.2e}")
     assert ey <= TOL and ex <= TOL and eb <= TOL and ew <= TOL
 
