@@ -200,12 +200,19 @@ typedef struct loqt_merge_desc {
 } loqt_merge_desc;
 
 /*
- * loqt_merge_requant_batched -- loqt_merge_requant over n_layers layers (descs: HOST array),
- * enqueued back to back on one stream; layers are independent.  Every descriptor is checked
- * before the first launch.
+ * loqt_merge_requant_batched -- loqt_merge_requant over n_layers layers (descs: HOST array; Alg. 1 line 5
+ * for a whole block or model, sec. 2.4 "layer by layer").  Layers are independent; every descriptor is
+ * checked before the first launch.  The layers go out in groups of consecutive layers: one launch expands
+ * the P_q of a group into the workspace and one launch runs the merge tiles of all its layers, so that a
+ * layer's ramp-up, last partly filled round and launch gap are filled with the next layer's tiles.  A group
+ * holds as many layers as the workspace has room for (at most 24).  ws_bytes must be at least the largest
+ * loqt_workspace_bytes(LOQT_OP_MERGE, ...) of any layer (then every group is one layer);
+ * loqt_merge_batched_workspace_bytes returns the size with which every group is full.  Results do not
+ * depend on the grouping: bit for bit those of n_layers calls of loqt_merge_requant.
  */
 loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc *descs,
                                        void *ws, size_t ws_bytes, void *hip_stream);
+size_t loqt_merge_batched_workspace_bytes(int n_layers, const loqt_merge_desc *descs);
 
 /*
  * Right-side projection variant (sec. 2.2: the one-sided projection is P^T G when the weight has

@@ -72,6 +72,8 @@ lib.loqt_merge_requant.restype = _i
 lib.loqt_merge_requant.argtypes = [_P(NF4MatC), _vp, _vp, _P(NF4MatC), _vp, _i64, _f, _vp, _sz, _vp]
 lib.loqt_merge_requant_batched.restype = _i
 lib.loqt_merge_requant_batched.argtypes = [_i, _P(MergeDescC), _vp, _sz, _vp]
+lib.loqt_merge_batched_workspace_bytes.restype = _sz
+lib.loqt_merge_batched_workspace_bytes.argtypes = [_i, _P(MergeDescC)]
 lib.loqt_linear_fwd_right.restype = _i
 lib.loqt_linear_fwd_right.argtypes = lib.loqt_linear_fwd.argtypes
 lib.loqt_linear_bwd_right.restype = _i
@@ -248,7 +250,11 @@ def make_merge_descs(layers):
     return arr
 
 
-def merge_descs_workspace_bytes(descs) -> int:
+def merge_descs_workspace_bytes(descs, full_groups: bool = True) -> int:
+    """Workspace for loqt_merge_requant_batched: the size with which every group of layers is full (default), or
+    the minimum (the largest single-layer need: groups of one layer)."""
+    if full_groups:
+        return max(int(lib.loqt_merge_batched_workspace_bytes(len(descs), descs)), 256)
     return max([loqt_workspace_bytes(OP_MERGE, 0, d.Wq.rows, d.Wq.cols, d.Pq.cols) for d in descs] + [256])
 
 

@@ -699,11 +699,54 @@ loqt_status loqt_merge_requant_batched(int n_layers, const loqt_merge_desc* desc
                              descs[i].ld_B));
         LOQT_TRY(check_merge_ws(&descs[i].Wq, &descs[i].Pq, ws, ws_bytes));
     }
-    // layers run back to back on one stream, so they can share the workspace
-    for (int i = 0; i < n_layers; ++i)
-        LOQT_TRY(merge_checked(&descs[i].Wq, descs[i].codes_out, descs[i].absmax_out, &descs[i].Pq, descs[i].B,
-                               descs[i].ld_B, descs[i].s, ws, (hipStream_t)hip_stream));
+    // Layers that take the pre-pass form go out in groups: one launch expands the P_q of the group into the
+    // workspace, one launch runs the merge tiles of all its layers.  A group holds as many consecutive layers as
+    // the workspace has room for (at most MERGE_GROUP_MAX); with the minimum workspace that is one layer at a
+    // time, the same kernels, the same bits.  Layers on the fused form (narrow weights) run one by one.
+    hipStream_t st = (hipStream_t)hip_stream;
+    int i = 0;
+    while (i < n_layers) {
+        if (!use_prepass_merge(descs[i].Wq.cols)) {
+            LOQT_TRY(merge_checked(&descs[i].Wq, descs[i].codes_out, descs[i].absmax_out, &descs[i].Pq, descs[i].B,
+                                   descs[i].ld_B, descs[i].s, ws, st));
+            ++i;
+            continue;
+        }
+        MergeGroupLayer layers[MERGE_GROUP_MAX];
+        DequantGroupItem deq[MERGE_GROUP_MAX];
+        int n = 0;
+        size_t used = 0;
+        while (i + n < n_layers && n < MERGE_GROUP_MAX && use_prepass_merge(descs[i + n].Wq.cols)) {
+            const loqt_merge_desc& d = descs[i + n];
+            const int64_t out = d.Wq.rows, in = d.Wq.cols, r = d.Pq.cols;
+            const size_t need = merge_ws_bytes(out, in, r);
+            if (n > 0 && used + need > ws_bytes) break;
+            uint16_t* Pb = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(ws) + used);
+            const int64_t ldr = (int64_t)round_up(r, 8);
+            deq[n] = DequantGroupItem{d.Pq.codes, d.Pq.absmax, Pb, out, d.Pq.ld, ldr, (int)r};
+            layers[n] = MergeGroupLayer{Pb, d.B, ldr, d.ld_B, d.Wq.codes, d.Wq.absmax, d.codes_out, d.absmax_out,
+                                        d.Wq.ld, (int)out, (int)in, (int)r, d.s};
+            used += need;
+            ++n;
+        }
+        LOQT_HIP(launch_dequantize_grouped(deq, n, st, SLOT_PREPASS));
+        LOQT_HIP(launch_merge_grouped(SLOT_MERGE, true, layers, n, st));
+        i += n;
+    }
     return LOQT_OK;
+}
+
+size_t loqt_merge_batched_workspace_bytes(int n_layers, const loqt_merge_desc* descs) {
+    if (n_layers <= 0 || !descs) return 0;
+    // the largest sum over MERGE_GROUP_MAX consecutive layers: with that much every group is full
+    size_t best = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        size_t sum = 0;
+        for (int k = i; k < n_layers && k < i + MERGE_GROUP_MAX; ++k)
+            sum += merge_ws_bytes(descs[k].Wq.rows, descs[k].Wq.cols, descs[k].Pq.cols);
+        best = std::max(best, sum);
+    }
+    return best;
 }
 
 int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in) {

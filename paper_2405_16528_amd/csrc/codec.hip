@@ -1,6 +1,8 @@
 // NF4 block codec kernels (paper sec. 5.1): stand-alone quantise and dequantise.
 // Both are pure HBM streams: 4 + 0.5625 bytes per element for the encoder,
 // 0.5625 + 2 (bf16) or 4 (fp32) for the decoder.
+#include <string.h>
+
 #include <mutex>
 
 #include "loqt_internal.h"
@@ -101,6 +103,52 @@ __global__ __launch_bounds__(256) void nf4_dequantize_kernel(const uint8_t* __re
             } else {
                 for (int e = 0; e < 8 && j0 + e < cols; ++e) dst[e] = v[e];
             }
+        }
+    }
+}
+
+// The same for several matrices in one launch (the deq(P) of the layers of a grouped merge): every work-group
+// belongs to one matrix and walks it with that matrix's share of the grid.  Descriptors travel in the kernel
+// argument block.
+struct DequantGroupParams {
+    int n;
+    DequantGroupItem it[MERGE_GROUP_MAX];
+    int block_end[MERGE_GROUP_MAX];
+};
+static_assert(sizeof(DequantGroupParams) <= 4096, "kernel arguments are limited to 4 KB");
+
+__global__ __launch_bounds__(256) void nf4_dequantize_grouped_kernel(const DequantGroupParams g) {
+    __shared__ float lut[16];
+    if (threadIdx.x < 16) lut[threadIdx.x] = kNf4Levels[threadIdx.x];
+    __syncthreads();
+    int li = 0;
+    while (li + 1 < g.n && (int)blockIdx.x >= g.block_end[li]) ++li;  // wave-uniform
+    const int first = li ? g.block_end[li - 1] : 0, nblk = g.block_end[li] - first;
+    const DequantGroupItem& it = g.it[li];
+    const int cols = it.cols;
+    const int gpr = (cols + 7) >> 3;
+    const int64_t ngroups = it.rows * gpr;
+    for (int64_t gi = (int64_t)((int)blockIdx.x - first) * 256 + threadIdx.x; gi < ngroups; gi += (int64_t)nblk * 256) {
+        const int64_t row = gi / gpr;
+        const int j0 = (int)(gi - row * gpr) * 8;
+        const uint32_t word = *reinterpret_cast<const uint32_t*>(it.codes + row * (it.ld_q >> 1) + (j0 >> 1));
+        const float m = it.absmax[row * (it.ld_q >> 6) + (j0 >> 6)];
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t c = (word >> (8 * (e >> 1) + ((e & 1) ? 0 : 4))) & 15u;
+            v[e] = m * lut[c];
+        }
+        uint16_t* dst = it.out + row * it.ld_out + j0;
+        if (j0 + 8 <= cols) {
+            uint4 o;
+            o.x = pack_bf16(v[0], v[1]);
+            o.y = pack_bf16(v[2], v[3]);
+            o.z = pack_bf16(v[4], v[5]);
+            o.w = pack_bf16(v[6], v[7]);
+            *reinterpret_cast<uint4*>(dst) = o;
+        } else {
+            for (int e = 0; e < 8 && j0 + e < cols; ++e) dst[e] = (uint16_t)(pack_bf16(v[e], 0.f) & 0xffffu);
         }
     }
 }
@@ -347,6 +395,22 @@ hipError_t launch_dequantize(const uint8_t* codes, const float* absmax, int64_t 
     else
         hipLaunchKernelGGL(nf4_dequantize_kernel<0>, dim3(grid), dim3(256), 0, st, codes, absmax, rows,
                            (int)cols, ld_q, out, ld_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_dequantize_grouped(const DequantGroupItem* items, int n, hipStream_t st, int slot) {
+    if (n < 1 || n > MERGE_GROUP_MAX) return hipErrorInvalidValue;
+    TimedLaunch tl(slot, st);
+    DequantGroupParams g;
+    memset(&g, 0, sizeof(g));
+    g.n = n;
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+        g.it[i] = items[i];
+        total += grid_for(items[i].rows * ((items[i].cols + 7) >> 3), 256 * 4);  // about four groups of 8 per lane
+        g.block_end[i] = total;
+    }
+    hipLaunchKernelGGL(nf4_dequantize_grouped_kernel, dim3((unsigned)total), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 

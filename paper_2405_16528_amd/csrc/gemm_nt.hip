@@ -31,6 +31,8 @@
 //  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in 8-row groups so that the
 //    work-groups sharing an L2 also share operand panels.
 // The 256x256 kernels use every vector register; tests/test_isa_guard.py checks their generated loop.
+#include <string.h>
+
 #include <type_traits>
 
 #include "loqt_internal.h"
@@ -68,8 +70,10 @@ struct NtCfg {
     static constexpr int SMEM = (SMEM_MAIN > SMEM_EPI ? SMEM_MAIN : SMEM_EPI) + 64;
 };
 
+// One output tile.  L: index of the tile in the walk order described above (tiles past the end return at once);
+// split: slice of the contraction (EPI_F32_SPLITK), else 0.
 template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
-__global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
+__device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, const int split) {
     using Cfg = NtCfg<BM, BN, NS>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE;
     constexpr int NM = TM * TN;  // MFMAs per k16 step
@@ -84,8 +88,6 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     // ---- tile of this work-group: contiguous range per XCD, groups of GM tile rows inside
     const int tiles_m = (p.M + BM - 1) / BM;
     const int tiles_n0 = (p.N + BN - 1) / BN, tiles_n = tiles_n0 + (p.Nx + BN - 1) / BN;
-    const int per_xcd = gridDim.x >> 3;
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (L >= tiles_m * tiles_n) return;
     constexpr int GM = (EPI == EPI_BF16 && !ARC && !BRC) ? 4 : 8;  // measured per operand layout
     const int gid = L / (GM * tiles_n);
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     int kt_begin = 0, kt_end = nkt0 + nkt1;
     if (EPI == EPI_F32_SPLITK) {
         const int per = (kt_end + p.splits - 1) / p.splits;
-        kt_begin = blockIdx.y * per;
+        kt_begin = split * per;
         kt_end = min(kt_end, kt_begin + per);
     }
 
@@ -759,11 +761,11 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
         }
         }
     } else if (EPI == EPI_F32_SPLITK || EPI == EPI_FOLD_F32) {
-        // fp32 results, 16 bytes per lane (row m, 4 consecutive n).  EPI_F32_SPLITK: slice blockIdx.y of the
+        // fp32 results, 16 bytes per lane (row m, 4 consecutive n).  EPI_F32_SPLITK: slice `split` of the
         // contraction.  EPI_FOLD_F32 (M = out, N = in): the dense merged weight of Alg. 1 line 5,
         // fma(alpha, acc, fl32(absmax * q[code])), the same expression the merge epilogue quantises.
         float* C = reinterpret_cast<float*>(p.C);
-        if (EPI == EPI_F32_SPLITK) C += (int64_t)blockIdx.y * p.M * p.ldc;
+        if (EPI == EPI_F32_SPLITK) C += (int64_t)split * p.M * p.ldc;
         float* lut = reinterpret_cast<float*>(smem);
         if (EPI == EPI_FOLD_F32) {
             if (tid < 16) lut[tid] = kNf4Levels[tid];
@@ -921,6 +923,61 @@ __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     }
 }
 
+// Work-groups are dealt to the 8 XCDs round-robin by the hardware; each XCD walks a contiguous range of tiles.
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
+__global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
+    const int per_xcd = gridDim.x >> 3;
+    nt_gemm_tile<BM, BN, EPI, ARC, BRC, NS>(p, (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), blockIdx.y);
+}
+
+// The merges of several layers (Alg. 1 line 5, one layer after the other) as ONE launch: the tiles of all layers
+// form one grid, so the prologue and epilogue of one layer's tiles overlap with the products of the next layer's
+// instead of every layer paying its own ramp-up, tail round and launch gap.  The per-layer descriptors travel in
+// the kernel argument block itself (no device-side table to fill, nothing to allocate, capture-safe), which
+// bounds a group at MERGE_GROUP_MAX layers.  per_xcd_end: running total of the tiles each XCD has walked when it
+// is through with this layer.
+struct MergeGroupItem {
+    const void* A;      // left operand of s * A B: deq(P) in bf16, out x r, K contiguous
+    const void* B;      // right operand: r x in stored K x rows (BRC) or in x r stored rows x K
+    int64_t lda, ldb;
+    const uint8_t* w_codes;
+    const float* w_absmax;
+    uint8_t* out_codes;
+    float* out_absmax;
+    int64_t w_ld;
+    int M, N, K, w_cols;
+    float alpha;
+    int per_xcd_end;
+};
+struct MergeGroupParams {
+    int n;
+    MergeGroupItem it[MERGE_GROUP_MAX];
+};
+static_assert(sizeof(MergeGroupParams) <= 4096, "kernel arguments are limited to 4 KB");
+
+template <bool BRC>
+__global__ __launch_bounds__(256) void nt_merge_grouped_kernel(const MergeGroupParams g) {
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    int li = 0;
+    while (li + 1 < g.n && j >= g.it[li].per_xcd_end) ++li;  // wave-uniform
+    const int start = li ? g.it[li - 1].per_xcd_end : 0;
+    const MergeGroupItem& it = g.it[li];
+    GemmParams p;
+    p.A[0].ptr = it.A, p.A[0].absmax = nullptr, p.A[0].ld = it.lda, p.A[0].rows = it.M, p.A[0].K = it.K;
+    p.B[0].ptr = it.B, p.B[0].absmax = nullptr, p.B[0].ld = it.ldb, p.B[0].rows = it.w_cols, p.B[0].K = it.K;
+    p.A[1].ptr = nullptr, p.A[1].absmax = nullptr, p.A[1].ld = 0, p.A[1].rows = 0, p.A[1].K = 0;
+    p.B[1] = p.A[1];
+    p.Bx = p.A[1];
+    p.M = it.M, p.N = it.N, p.alpha = it.alpha;
+    p.C = nullptr, p.ldc = 0, p.splits = 1;
+    p.Cx = nullptr, p.ldcx = 0, p.Nx = 0, p.alphax = 0.f;
+    p.w_codes = it.w_codes, p.w_absmax = it.w_absmax, p.out_codes = it.out_codes, p.out_absmax = it.out_absmax;
+    p.w_ld = it.w_ld, p.w_cols = it.w_cols;
+    p.w_bf16 = nullptr, p.w_bf16_ld = 0, p.w_f32 = nullptr, p.w_f32_ld = 0, p.e_out = nullptr, p.e_ld = 0;
+    const int per_xcd = it.per_xcd_end - start;
+    nt_gemm_tile<128, 128, EPI_MERGE, false, BRC>(p, xcd * per_xcd + (j - start), 0);
+}
+
 template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
     auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS>;
@@ -1025,6 +1082,47 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
 }  // namespace
 
 int g_nt_tile_override = 0;
+
+hipError_t launch_merge_grouped(int slot, bool b_rc, const MergeGroupLayer* layers, int n, hipStream_t st) {
+    if (n < 1 || n > MERGE_GROUP_MAX) return hipErrorInvalidValue;
+    TimedLaunch tl(slot, st);
+    MergeGroupParams g;
+    memset(&g, 0, sizeof(g));
+    g.n = n;
+    int per_xcd_total = 0;
+    for (int i = 0; i < n; ++i) {
+        const MergeGroupLayer& l = layers[i];
+        MergeGroupItem& it = g.it[i];
+        it.A = l.A, it.lda = l.lda, it.B = l.B, it.ldb = l.ldb;
+        it.w_codes = l.w_codes, it.w_absmax = l.w_absmax, it.out_codes = l.out_codes, it.out_absmax = l.out_absmax;
+        it.w_ld = l.w_ld, it.M = l.out, it.N = (int)l.w_ld, it.K = l.r, it.w_cols = l.in, it.alpha = l.s;
+        const int tiles = ((l.out + 127) / 128) * (int)((l.w_ld + 127) / 128);
+        per_xcd_total += (tiles + 7) / 8;
+        it.per_xcd_end = per_xcd_total;
+    }
+    constexpr int smem = NtCfg<128, 128, 2>::SMEM;
+    const dim3 grid((unsigned)per_xcd_total * 8u);
+    if (b_rc) {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_merge_grouped_kernel<true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(nt_merge_grouped_kernel<true>, grid, dim3(256), smem, st, g);
+    } else {
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_merge_grouped_kernel<false>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(nt_merge_grouped_kernel<false>, grid, dim3(256), smem, st, g);
+    }
+    return hipGetLastError();
+}
 
 // a_rc / b_rc: the operand is stored K x rows (rows contiguous) instead of rows x K
 hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st) {

@@ -235,6 +235,32 @@ int gemm_db_splits(int64_t T, int64_t r, int64_t in);
 // large-token path (gemm_nt.hip): bf16 operands stored rows x K (K contiguous) or, with the
 // a_rc / b_rc flag, K x rows (rows contiguous; Operand::ld is the pitch of that stored matrix)
 hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmParams& p, hipStream_t st);
+// several merges as one launch of 128x128 tiles (EPI_MERGE over the tiles of all layers); at most MERGE_GROUP_MAX
+// layers per launch.  A: deq(P) in bf16 (out x r, pitch lda); B: the trainable factor, r x in stored K x rows
+// (b_rc) or in x r stored rows x K; the rest as in GemmParams.
+constexpr int MERGE_GROUP_MAX = 24;
+struct MergeGroupLayer {
+    const void* A;
+    const void* B;
+    int64_t lda, ldb;
+    const uint8_t* w_codes;
+    const float* w_absmax;
+    uint8_t* out_codes;
+    float* out_absmax;
+    int64_t w_ld;
+    int out, in, r;
+    float s;
+};
+// NF4 -> bf16 of up to MERGE_GROUP_MAX matrices in one launch
+struct DequantGroupItem {
+    const uint8_t* codes;
+    const float* absmax;
+    uint16_t* out;
+    int64_t rows, ld_q, ld_out;
+    int cols;
+};
+hipError_t launch_dequantize_grouped(const DequantGroupItem* items, int n, hipStream_t st, int slot);
+hipError_t launch_merge_grouped(int slot, bool b_rc, const MergeGroupLayer* layers, int n, hipStream_t st);
 // tuning aid for benchmarks: 0 = choose by shape, 1 = 256x256, 2 = 256x128, 3 = 128x128 tiles
 extern int g_nt_tile_override;
 // how launch_gemm_nt lays out a bf16-output product (EPI_BF16) that is large enough for 256x256 tiles, and its

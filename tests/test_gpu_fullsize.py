@@ -166,3 +166,81 @@ def test_full_size_large_low_rank_term(workload, layer):
     """B ~ N(0, 2e-2): the rank-r term is a quarter of the effective weight instead of one per cent, so an error in
     it cannot hide under the tolerance of the whole."""
     _full_compare(workload, layer, 2e-2, 1.0, check_weff=(layer == "q"))
+
+
+def test_13b_merge_sweep_batched():
+    """The merge of a whole 13B model (40 blocks x 7 projections, 7.1 GB of NF4 weights) as one batched call, in
+    place, as bench.py times it.  Three layers -- the first, one in the middle, the last -- carry seeded weights
+    quantised by the oracle and are checked against it on sampled rows (policy of reading R14); two of the filler
+    layers are checked bit for bit against single calls of loqt_merge_requant on copies of their inputs."""
+    from tests import gpu_util as G
+    from paper_2405_16528_amd import binding as L
+    L.set_path(L.PATH_AUTO)
+    wl = synth.WORKLOADS["13b_block"]
+    r, s = wl.r, 0.5
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    shapes = {}
+    for (_, out, inp) in wl.projections:
+        if (out, inp) not in shapes:
+            P = synth.orthonormal_f32(synth.rng_for(0, "sweep", out, inp, "P"), out, r)
+            Pq = O.nf4_quantize(P)
+            B = synth.normal_bf16(synth.rng_for(0, "sweep", out, inp, "B"), (r, inp), 1e-3)
+            shapes[(out, inp)] = (Pq, B, G.nf4_dev(*Pq), G.bf16_dev(B))
+    n_layers = wl.n_blocks * len(wl.projections)
+    checked = {0: None, n_layers // 2 + 4: None, n_layers - 1: None}  # q of block 0, gate of block 20, down of block 39
+    copies = {3: None, n_layers - 5: None}
+    layers = []
+    for li in range(n_layers):
+        name, out, inp = wl.projections[li % len(wl.projections)]
+        if li in checked:
+            W = synth.normal_f32(synth.rng_for(0, "sweep", li, "W"), (out, inp), 0.02)
+            Wq = O.nf4_quantize(W)
+            checked[li] = Wq
+            Wd = G.nf4_dev(*Wq)
+        else:
+            W = torch.empty((out, inp), device="cuda", dtype=torch.float32).normal_(0.0, 0.02, generator=gen)
+            Wd = L.nf4_quantize(W)
+        del W
+        if li in copies:
+            copies[li] = L.NF4Tensor(Wd.codes.clone(), Wd.absmax.clone(), out, inp, Wd.ld)
+        _, _, Pd, Bd = shapes[(out, inp)]
+        layers.append((Wd, None, Pd, Bd, s))  # in place
+    descs = L.make_merge_descs(layers)
+    ws = torch.empty(L.merge_descs_workspace_bytes(descs), dtype=torch.uint8, device="cuda")
+    L.loqt_merge_requant_batched(descs, ws)
+    torch.cuda.synchronize()
+    rng = synth.rng_for(0, "sweep-rows")
+    for li, Wq in checked.items():
+        name, out, inp = wl.projections[li % len(wl.projections)]
+        Pq, B, _, _ = shapes[(out, inp)]
+        rows = np.unique(np.concatenate([[0, out - 1], rng.choice(out, size=40, replace=False)]))
+        c, a, _, _ = G.nf4_host(layers[li][0])
+        rate = _merge_policy_check(c[rows], a[rows], (Wq[0][rows], Wq[1][rows]), (Pq[0][rows], Pq[1][rows]), B, s)
+        print(f"sweep layer {li} ({name} {out}x{inp}): code mismatch rate on {len(rows)} rows {rate:.2e}")
+        assert rate <= 1e-3
+    for li, src in copies.items():
+        name, out, inp = wl.projections[li % len(wl.projections)]
+        _, _, Pd, Bd = shapes[(out, inp)]
+        single = L.loqt_merge_requant(src, Pd, Bd, s, out=L.NF4Tensor.empty(out, inp))
+        torch.cuda.synchronize()
+        assert torch.equal(single.codes, layers[li][0].codes) and torch.equal(single.absmax, layers[li][0].absmax)
+    # the grouping does not change a bit: the same sweep over the first block with the minimum workspace
+    # (groups of one layer) against groups as large as the workspace allows
+    first = []
+    for li in range(7):
+        name, out, inp = wl.projections[li]
+        _, _, Pd, Bd = shapes[(out, inp)]
+        W = torch.empty((out, inp), device="cuda", dtype=torch.float32).normal_(0.0, 0.02, generator=gen)
+        first.append((L.nf4_quantize(W), Pd, Bd))
+        del W
+    outs = []
+    for full in (True, False):
+        dst = [L.NF4Tensor.empty(w.rows, w.cols) for (w, _, _) in first]
+        d = L.make_merge_descs([(w, o, p, b, s) for (w, p, b), o in zip(first, dst)])
+        L.loqt_merge_requant_batched(d, torch.empty(L.merge_descs_workspace_bytes(d, full_groups=full),
+                                                    dtype=torch.uint8, device="cuda"))
+        torch.cuda.synchronize()
+        outs.append(dst)
+    for a, b in zip(*outs):
+        assert torch.equal(a.codes, b.codes) and torch.equal(a.absmax, b.absmax)

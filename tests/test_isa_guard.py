@@ -35,7 +35,7 @@ def assembly(tmp_path_factory):
 def _loop_blocks(asm, mangled_part):
     start = asm.index(mangled_part)
     start = asm.index("\n", start)
-    body = asm[start:asm.index("s_endpgm", start)]
+    body = asm[start:asm.index(".Lfunc_end", start)]  # (a function may hold more than one s_endpgm)
     blocks, label, lines = [], "entry", []
     for line in body.split("\n"):
         if re.match(r"^\.LBB\d+_\d+:", line):
