@@ -891,6 +891,16 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                 amax = fmaxf(amax, __shfl_xor(amax, 32));
                 Nf4BlockEncoder be;
                 be.set(amax);
+                // single-precision encoder first; the exact one again for the whole block when any lane of the
+                // wave has an element within rounding of a decision point (about one block in 10^4)
+                uint32_t code[32];
+                uint32_t near = 0;
+#pragma unroll
+                for (int e = 0; e < 32; ++e) code[e] = be.encode_fast(enc, v[e], near);
+                if (__any(near)) {
+#pragma unroll
+                    for (int e = 0; e < 32; ++e) code[e] = be.encode(enc, v[e]);
+                }
 #pragma unroll
                 for (int tt = 0; tt < 2; ++tt) {
                     uint32_t o[4];
@@ -899,7 +909,7 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                         const int q = 4 * tt + g;
                         uint32_t c[4];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) c[j] = be.encode(enc, v[4 * q + j]);
+                        for (int j = 0; j < 4; ++j) c[j] = code[4 * q + j];
                         if constexpr (EPI == EPI_COMP) {
                             const int nq = nb + tt * 32 + 8 * g + 4 * h;
                             float e[4];

@@ -74,6 +74,7 @@ __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v 
 struct Nf4EncTables {
     double mid[64];
     uint32_t c0[64];
+    float2 fast[64];  // {fl32(mid[k]), c0[k] as bits}: one 8-byte read for the single-precision path
 };
 
 // one entry per calling thread, k = 0..63 (entries above 32 are never addressed by finite data
@@ -89,13 +90,27 @@ __device__ __forceinline__ void nf4_enc_tables_fill(Nf4EncTables* t, int k) {
         if (j == c) m = kNf4Mid[j];
     t->mid[k] = m;
     t->c0[k] = (uint32_t)c;
+    t->fast[k] = make_float2((float)m, __uint_as_float((uint32_t)c));
 }
 
+// Two ways to the same code.  encode(): everything in fp64, exact for every finite block.  encode_fast(): the same
+// bucket rule in single precision, with the one comparison that decides taken against th32 = fl32(fl32(mid) * M).
+// th32 is within 2^-23 |mid M| < 2^-23 M of the exact threshold and d = w - th32 is computed to within 2^-24 |d|,
+// so whenever |d| > 2^-22 M its sign is the sign of the exact difference and the code is the exact one; otherwise
+// (about one element in a million) the caller's `near` flag is raised and the block is encoded again with
+// encode().  Blocks whose scale is outside [2^-100, 2^100] (where 16 / M, th32 or the guard could leave the normal
+// range) raise the flag for every element.  Callers test the flag wave-wide (__any), so the branch is uniform.
 struct Nf4BlockEncoder {
     double Md, scd;
+    float Mf, scf, guard;
+    uint32_t out_of_range;
     __device__ __forceinline__ void set(float absmax) {
-        Md = (double)(absmax > 0.f ? absmax : 1.f);
+        Mf = absmax > 0.f ? absmax : 1.f;
+        Md = (double)Mf;
         scd = 16.0 * __builtin_amdgcn_rcp(Md);
+        scf = 16.0f * __builtin_amdgcn_rcpf(Mf);
+        guard = Mf * 0x1p-22f;
+        out_of_range = (Mf >= 0x1p-100f && Mf <= 0x1p100f) ? 0u : 1u;
     }
     __device__ __forceinline__ uint32_t encode(const Nf4EncTables* t, float w) const {
         const double wd = (double)w;
@@ -104,6 +119,15 @@ struct Nf4BlockEncoder {
         const uint32_t k = (uint32_t)__double2loint(xd) & 63u;
         const double th = t->mid[k] * Md;  // exact
         return t->c0[k] + ((wd > th) ? 1u : 0u);
+    }
+    __device__ __forceinline__ uint32_t encode_fast(const Nf4EncTables* t, float w, uint32_t& near) const {
+        // 1.5 * 2^23 + 16 + 16 u, rounded to an integer by the addition itself: the low bits are k
+        const float xf = __builtin_fmaf(w, scf, 12582928.0f);
+        const uint32_t k = __float_as_uint(xf) & 63u;
+        const float2 e = t->fast[k];
+        const float d = w - e.x * Mf;
+        near |= (__builtin_fabsf(d) > guard) ? out_of_range : 1u;  // also raised by a NaN (never for finite data)
+        return __float_as_uint(e.y) + ((d > 0.f) ? 1u : 0u);
     }
 };
 

@@ -217,3 +217,55 @@ def test_decision_points_are_isolated_in_sixteenth_buckets():
         c0 = sum(1 for m in mids if m < left - guard)
         code = c0 + (1 if c0 < 15 and u > mids[c0] else 0)
         assert code == sum(1 for m in mids if u > m)
+
+
+def test_single_precision_decision_is_exact_outside_its_guard_band():
+    """An encoder may take the one deciding comparison in single precision: with th32 = fl32(fl32(mid_j) * M) and
+    d = fl32(w - th32), the sign of d is the sign of the exact w - mid_j M whenever |d| > 2^-22 M (th32 is within
+    2^-23 M of the exact threshold, d within 2^-24 |d| of w - th32), provided M is a normal number far from the
+    ends of the range.  Checked here in exact rational arithmetic on the values where it could fail: every fp32
+    neighbour of every threshold, at scales across the allowed range, and random elements; and the share of
+    random elements that fall inside the guard band (they take the exact path) is of the order 1e-6."""
+    q = [Fraction(float(v)) for v in O.NF4_LEVELS]
+    mids = [(q[j] + q[j + 1]) / 2 for j in range(15)]
+    mids32 = np.array([float(m) for m in mids], dtype=np.float32)  # fl32(mid): float(m) is exact (29 bits), then RNE
+    rng = np.random.default_rng(3)
+    scales = [np.float32(2.0) ** e for e in (-100, -60, -24, -7, 0, 5, 40, 100)]
+    scales += list((rng.uniform(1.0, 2.0, 6).astype(np.float32)) * np.float32(2.0) ** rng.integers(-90, 90, 6))
+    checked = 0
+    for M in scales:
+        M = np.float32(M)
+        guard = np.float32(M * np.float32(2.0 ** -22))
+        for j in range(15):
+            th32 = np.float32(mids32[j] * M)
+            exact_th = mids[j] * Fraction(float(M))
+            # the fp32 values around the threshold, a few steps to each side
+            w = th32
+            cand = [w]
+            lo = hi = w
+            for _ in range(40):
+                lo = np.nextafter(lo, np.float32(-np.inf), dtype=np.float32)
+                hi = np.nextafter(hi, np.float32(np.inf), dtype=np.float32)
+                cand += [lo, hi]
+            for w in cand:
+                d = np.float32(w - th32)
+                if abs(d) > guard:
+                    assert (d > 0) == (Fraction(float(w)) > exact_th), (float(M), j, float(w))
+                    checked += 1
+    assert checked > 1000
+    # random elements of random blocks: outside the guard band the fast decision equals the exact one
+    near = total = 0
+    for _ in range(40):
+        M = np.float32(rng.uniform(0.5, 2.0) * 2.0 ** rng.integers(-30, 30))
+        w = (rng.uniform(-1, 1, 20000) * M).astype(np.float32)
+        for j in range(15):
+            th32 = np.float32(mids32[j] * M)
+            d = (w - th32).astype(np.float32)
+            sure = np.abs(d) > np.float32(M * np.float32(2.0 ** -22))
+            # inside the band anything may happen (those elements take the exact path); outside, compare in float64,
+            # which decides correctly there (|w - mid M| > 2^-23 M, and mid M is exact in float64)
+            ref = w.astype(np.float64) > float(mids[j]) * float(M)
+            assert np.array_equal((d > 0)[sure], ref[sure])
+            near += int((~sure).sum())
+            total += w.size
+    assert near / total < 2e-5
