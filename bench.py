@@ -358,15 +358,18 @@ def flop_counts(synth, L, wl, mode):
     T, r = wl.T, wl.r
     f_fb = sum(synth.flops_fwd(T, o, i, r) + synth.flops_bwd(T, o, i, r) for (_, o, i) in wl.projections)
     saved = mode == "saved"
+    # the forward and the backward call choose separately (the backward one has Z at hand anyway)
     folded = {n: saved or L.resolved_path(L.OP_FWD, T, o, i) == L.PATH_FOLDED for (n, o, i) in wl.projections}
+    folded_b = {n: saved or L.resolved_path(L.OP_BWD, T, o, i) == L.PATH_FOLDED for (n, o, i) in wl.projections}
     k = {
         "gemm_u": sum(2 * T * i * r for (n, o, i) in wl.projections if not folded[n]),
         "gemm_y": sum(2 * T * o * (i + (0 if folded[n] else r)) for (n, o, i) in wl.projections),
         # folded: Z may ride along with dx ([dx | Z] = dy [W_eff | s deq(P)]); its flops are then in gemm_dx
-        "gemm_z+dx": sum(2 * T * o * (i + r) if folded[n] else 2 * T * (o * r + i * (o + r))
+        "gemm_z+dx": sum(2 * T * o * (i + r) if folded_b[n] else 2 * T * (o * r + i * (o + r))
                          for (n, o, i) in wl.projections),
         "gemm_db": sum(2 * T * r * i for (n, o, i) in wl.projections),
-        "fold_weight": sum((1 if saved else 2) * 2 * o * i * r for (n, o, i) in wl.projections if folded[n]),
+        "fold_weight": sum(2 * o * i * r * ((1 if folded[n] else 0) + (1 if folded_b[n] and not saved else 0))
+                           for (n, o, i) in wl.projections),
     }
     return f_fb, k, folded
 
@@ -627,8 +630,10 @@ def main():
                                    "the chosen implementation runs (folded: 2*out*in*r per fold instead of the "
                                    "rank-r products through every token)",
                         paths=["folded"] if mode == "saved" else
-                        sorted({["auto", "fused", "prepass", "folded"][L.resolved_path(L.OP_FWD, T, o, i)]
-                                for (_, o, i) in wl.projections})),
+                        {"fwd": sorted({["auto", "fused", "prepass", "folded"][L.resolved_path(L.OP_FWD, T, o, i)]
+                                        for (_, o, i) in wl.projections}),
+                         "bwd": sorted({["auto", "fused", "prepass", "folded"][L.resolved_path(L.OP_BWD, T, o, i)]
+                                        for (_, o, i) in wl.projections})}),
         "merge": merge,
         "other_mode": dict(fb_entry(o_fb, f_fb_o, f_exec_o), mode=other, step=step_text[other],
                            ms_per_whole_step=o_step, value=(f_fb + f_mg) / (o_step * 1e-3) / 1e12,

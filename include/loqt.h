@@ -396,7 +396,10 @@ loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int6
  *                      (dB = Z^T x).  Cheaper than carrying the rank-r term through every token
  *                      (2 T r (in + out) flop per pass) from T = out in / (in + out) tokens up.
  *   LOQT_PATH_AUTO   : forward and backward always take the pre-pass family (measured ahead of the
- *                      fused form at every token count from 16 up), folded when T (in + out) >= out in;
+ *                      fused form at every token count from 16 up), folded when T (in + out) >= out in --
+ *                      except that the backward pass, which has Z = s dy deq(P_q) at hand anyway, keeps the
+ *                      rank-r term as a second K segment of the dx product when out > 0.73 T (2 T r in flop at
+ *                      the rate of the large products instead of 2 out in r at the rate of the fold);
  *                      the merge is fused below 1024 columns (`in`), pre-pass above.
  * All compute the same quantities; results differ only in rounding order, within the stated
  * tolerance.

@@ -113,6 +113,17 @@ bool use_folded(int64_t T, int64_t out, int64_t in) {
     return T * (in + out) >= out * in;  // measured: still ahead at the break-even of the flop counts
 }
 
+// Backward pass: Z = s dy deq(P) exists anyway (dB needs it), so carrying the rank-r term as a second K segment of
+// the dx product costs only 2 T r in flop at the rate of the large products, against 2 out in r flop at the rate of
+// the fold (about half of that: short contraction, heavy epilogue) -- cheaper when the weight has many more rows
+// than the step has tokens.  Measured rates put the break-even near out = 0.73 T (7B gate / up at 8192 tokens and
+// every projection of the 13B block at 4096 tokens take the second-segment form, the square 7B projections fold).
+bool use_folded_bwd(int64_t T, int64_t out, int64_t in) {
+    if (!use_folded(T, out, in)) return false;
+    if (g_path != LOQT_PATH_AUTO) return true;
+    return (double)out <= 0.73 * (double)T;
+}
+
 inline size_t bf16_bytes(int64_t rows, int64_t cols) {
     return round_up((size_t)rows * (size_t)round_up(cols, 8) * 2, 256);
 }
@@ -560,7 +571,7 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
         float* part = reinterpret_cast<float*>(base + L.partials);
         const int64_t ldw = saved ? ld_saved : (int64_t)round_up(in, 8);
         LOQT_HIP(launch_dequantize(Pq->codes, Pq->absmax, out, r, Pq->ld, Pb, LOQT_BF16, ld_z, st, SLOT_PREPASS));
-        const bool folded = dx && (saved || use_folded(T, out, in));
+        const bool folded = dx && (saved || use_folded_bwd(T, out, in));
         // Z rides along with dx (one product [dx | Z] over the shared operand dy) when that is estimated to
         // take less time than the two launches: its tiles then fill a partly empty round of the dx product
         bool z_with_dx = false;
@@ -752,6 +763,7 @@ size_t loqt_merge_batched_workspace_bytes(int n_layers, const loqt_merge_desc* d
 int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in) {
     if (op == LOQT_OP_MERGE) return use_prepass_merge(in) ? LOQT_PATH_PREPASS : LOQT_PATH_FUSED;
     if (!use_prepass(T)) return LOQT_PATH_FUSED;
+    if (op == LOQT_OP_BWD) return use_folded_bwd(T, out, in) ? LOQT_PATH_FOLDED : LOQT_PATH_PREPASS;
     return use_folded(T, out, in) ? LOQT_PATH_FOLDED : LOQT_PATH_PREPASS;
 }
 

@@ -675,20 +675,66 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
             if (tid < 16) lut[tid] = kNf4Levels[tid];
             __syncthreads();
         }
-        char* ebuf = smem + wave * (WTM * EPITCH);
+        // The fold stages 32 rows at a time (the same 32 rows of LDS for every block of rows: the LDS operations of a
+        // wave complete in order), which leaves room for the old codes of the whole tile beside them.
+        constexpr bool FOLD = EPI == EPI_FOLD;
+        constexpr int EROWS = FOLD ? 32 : WTM;
+        char* ebuf = smem + wave * (EROWS * EPITCH);
         const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
+        // Fold: the old codes of the wave's rows (WTN / 2 bytes each) come in as direct-to-LDS loads, all issued at
+        // once, and the block scales as ordinary loads into registers: one round trip to memory for the tile instead
+        // of one per 32x32 piece (fetched piece by piece, a piece ahead of its use, the epilogue took as long as
+        // eleven k-tiles of the product, most of it waiting for these loads).
+        constexpr int CROW = WTN / 2;              // code bytes per row of the wave tile
+        constexpr int LPR = WTN / 32;              // lanes (16 bytes each) per row
+        constexpr int RPI = 64 / LPR;              // rows per load instruction
+        constexpr int NCI = FOLD ? WTM / RPI : 1;  // load instructions
+        char* cbuf = smem + 4 * EROWS * EPITCH + wave * (WTM * CROW);
+        float amr[FOLD ? TM : 1][FOLD ? TN / 2 : 1];
+        if constexpr (FOLD) {
+            const int wm_s = wave_s >> 1, wn_s = wave_s & 1;
+            const int crow = lane / LPR, cch = lane % LPR;
+            const int nt = n0 + wn * WTN + cch * 32;
+            const uint32_t lds_c = (uint32_t)(uintptr_t)LOQT_LDS_PTR(smem) + (uint32_t)(4 * EROWS * EPITCH) +
+                                   (uint32_t)(wave_s * (WTM * CROW));
+            const uint32_t off = (uint32_t)crow * (uint32_t)ldb + (uint32_t)cch * 16u;
+#pragma unroll
+            for (int i = 0; i < NCI; ++i) {
+                const int m = m0 + wm * WTM + i * RPI + crow;
+                const uint64_t mask = __ballot(m < p.M && nt < p.w_ld);
+                const uint8_t* base = p.w_codes + (int64_t)(m0 + wm_s * WTM + i * RPI) * ldb + ((n0 + wn_s * WTN) >> 1);
+                asm volatile(
+                    "s_mov_b32 m0, %2\n\t"
+                    "s_mov_b64 exec, %3\n\t"
+                    "global_load_lds_dwordx4 %0, %1\n\t"
+                    "s_mov_b64 exec, -1"
+                    :
+                    : "v"(off), "s"(base), "s"(lds_c + (uint32_t)(i * 1024)), "s"(mask)
+                    : "memory");
+            }
+#pragma unroll
+            for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+                for (int b = 0; b < TN / 2; ++b) {
+                    const int m = m0 + wm * WTM + ti * 32 + frow;
+                    const int nb = n0 + wn * WTN + b * 64;
+                    amr[ti][b] = (m < p.M && nb < p.w_ld) ? p.w_absmax[m * lda + (nb >> 6)] : 0.f;
+                }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // each wave reads back only what it loaded itself
+        }
         // A block of rows is staged through the wave's private LDS region and leaves as whole 16-byte row
         // segments right after it has been computed (LDS operations of one wave complete in order, so no
         // barrier), so that the stores of one block are under way while the next one is computed.
         constexpr int CPR = WTN / 8;  // 16-byte chunks per row
         uint16_t* C = reinterpret_cast<uint16_t*>(part1 ? p.Cx : p.C);
         const int64_t ldc = part1 ? p.ldcx : p.ldc;
-        auto store_rows = [&](int row0, int nrows) {  // rows row0 .. row0+nrows-1 of the wave tile
+        // rows row0 .. row0+nrows-1 of the wave tile, staged from row erow0 of the staging region on
+        auto store_rows = [&](int row0, int nrows, int erow0) {
 #pragma unroll 4
             for (int it = 0; it < nrows * CPR / 64; ++it) {
                 const int idx = it * 64 + lane, row = row0 + idx / CPR, ch = idx % CPR;
                 const int m = m0 + wm * WTM + row, n = n0 + wn * WTN + ch * 8;
-                const uint4 v = *reinterpret_cast<const uint4*>(ebuf + row * EPITCH + ch * 16);
+                const uint4 v = *reinterpret_cast<const uint4*>(ebuf + (erow0 + idx / CPR) * EPITCH + ch * 16);
                 if (m < p.M) {
                     uint16_t* dst = C + (int64_t)m * ldc + n;
                     if (n + 8 <= N) {
@@ -712,7 +758,7 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                                                pack_bf16(alpha * acc16[ti][tj][2], alpha * acc16[ti][tj][3]));
                     *reinterpret_cast<uint2*>(ebuf + (ti * 16 + frow16) * EPITCH + (tj * 16 + 4 * q4) * 2) = v;
                 }
-                if (ti & 1) store_rows((ti - 1) * 16, 32);
+                if (ti & 1) store_rows((ti - 1) * 16, 32, (ti - 1) * 16);
             }
         } else {
 #pragma unroll
@@ -723,13 +769,13 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                 // lanes of a pair load them; this lane uses the half-words (lane >> 5) of each dword)
                 uint32_t cw4[4] = {0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};
                 float am = 0.f;
-                if (EPI == EPI_FOLD) {
+                if constexpr (FOLD) {
                     const int m = m0 + wm * WTM + ti * 32 + frow;
                     const int nt = n0 + wn * WTN + tj * 32;
                     if (m < p.M && nt < p.w_ld) {
-                        const uint4 c = *reinterpret_cast<const uint4*>(p.w_codes + m * ldb + (nt >> 1));
+                        const uint4 c = *reinterpret_cast<const uint4*>(cbuf + (ti * 32 + frow) * CROW + tj * 16);
                         cw4[0] = c.x, cw4[1] = c.y, cw4[2] = c.z, cw4[3] = c.w;
-                        am = p.w_absmax[m * lda + (nt >> 6)];
+                        am = amr[ti][tj >> 1];
                     }
                 }
 #pragma unroll
@@ -754,10 +800,10 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                         v3 += am * lut[nib4(cw, 3)];
                     }
                     const uint2 v = make_uint2(pack_bf16(v0, v1), pack_bf16(v2, v3));
-                    *reinterpret_cast<uint2*>(ebuf + (ti * 32 + frow) * EPITCH + (tj * 32 + 8 * g + 4 * h) * 2) = v;
+                    *reinterpret_cast<uint2*>(ebuf + ((FOLD ? 0 : ti * 32) + frow) * EPITCH + (tj * 32 + 8 * g + 4 * h) * 2) = v;
                 }
             }
-            store_rows(ti * 32, 32);
+            store_rows(ti * 32, 32, FOLD ? 0 : ti * 32);
         }
         }
     } else if (EPI == EPI_F32_SPLITK || EPI == EPI_FOLD_F32) {

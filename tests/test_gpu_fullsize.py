@@ -95,7 +95,14 @@ def test_full_size_sampled(workload, layer):
         descs = L.make_merge_descs([(Wd, merged2, Pd, B, s)])
         L.loqt_merge_requant_batched(descs)
         torch.cuda.synchronize()
-        assert torch.equal(y2, y) and torch.equal(dx2, dx) and torch.equal(dB2, dB)
+        assert torch.equal(y2, y) and torch.equal(dB2, dB)
+        if L.resolved_path(L.OP_BWD, T, out, inp) == L.PATH_FOLDED:
+            assert torch.equal(dx2, dx)
+        else:
+            # the plain backward call kept the rank-r term as a second K segment here (many more rows than tokens):
+            # other kernels, so the saved pair's dx is compared with the oracle on its own
+            ex2, fx2, _ = G.bf16_output_report(G.bf16_host(dx2[Id]), dx_ref)
+            assert ex2 <= max(TOL, fx2 + 8e-3)
         assert torch.equal(merged2.codes, merged.codes) and torch.equal(merged2.absmax, merged.absmax)
         del w_eff, y2, dx2, dB2, merged2
 
