@@ -132,6 +132,29 @@ size_t bwd_z_bytes(int64_t T, int64_t r) { return bf16_bytes(T, r); }
 // Workspace layouts of the pre-pass family.  Products take their operands in whichever orientation
 // they are stored (rows x K or K x rows), so nothing is ever transposed: the only pre-passes are NF4
 // expansions, one per NF4 operand and call.
+// Number of slices of the contraction for a product whose result is summed from fp32 slices (dB = Z^T x and its
+// relatives: M x N outputs, contraction K).  Estimated duration in k-tile steps: rounds of work-groups (256 tiles
+// of 256x128 with one work-group per compute unit from 1024 rows up, 512 tiles of 128x128 with two per unit below;
+// the launcher makes the same choice) times the k-tiles per slice plus a fixed prologue / epilogue, plus the slices'
+// own traffic (each is written once and read once by the reduction: M N 8 bytes against the ~12 MB the chip moves
+// in one k-tile step when the slices stay in the Infinity Cache).  A slice is at least 512 deep.
+int choose_splits(int64_t M, int64_t N, int64_t K) {
+    auto cdiv = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
+    const bool wide = M >= 1024;
+    const int64_t tiles = wide ? cdiv(M, 256) * cdiv(N, 128) : cdiv(M, 128) * cdiv(N, 128);
+    const int64_t slots = wide ? 256 : 512;
+    const int64_t nkt = cdiv(K, 64);
+    const double per_slice = (double)M * (double)N * 8.0 / 12.0e6;
+    int best = 1;
+    double best_cost = 0.0;
+    for (int s = 1; s <= 16; ++s) {
+        if (s > 1 && nkt / s < 8) break;
+        const double cost = (double)cdiv(tiles * s, slots) * ((double)cdiv(nkt, s) + 6.0) + per_slice * s;
+        if (s == 1 || cost < best_cost) best = s, best_cost = cost;
+    }
+    return best;
+}
+
 struct FwdWs {
     size_t U, Wb, Pb, total;  // U = s x B^T; Wb = deq(W) or W_eff; Pb = deq(P)
     FwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
@@ -151,13 +174,7 @@ struct BwdWs {
         Pb = Wb + bf16_bytes(out, in);
         partials = Pb + bf16_bytes(out, r);
         ldp = (int64_t)round_up(in, 4);
-        // split the contraction over T so that about two 128x128 work-groups per compute unit are
-        // resident (at least two slices, each at least 512 deep)
-        const int64_t tiles = ((r + 127) / 128) * ((in + 127) / 128);
-        const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, T / 512));
-        int64_t s = std::max<int64_t>(2, (512 + tiles / 2) / tiles);
-        s = std::min(s, max_s);
-        splits = (int)s;
+        splits = choose_splits(r, in, T);
         total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
     }
 };
@@ -183,9 +200,7 @@ struct InitWs {
         Pb = 0;
         E = Pb + round_up((size_t)out * (size_t)ldr * 2, 256);
         partials = E + round_up((size_t)out * (size_t)lde * 2, 256);
-        const int64_t tiles = ((r + 127) / 128) * ((in + 127) / 128);
-        const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, out / 512));
-        splits = (int)std::min(std::max<int64_t>(2, (512 + tiles / 2) / tiles), max_s);
+        splits = choose_splits(r, in, out);
         total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
     }
 };
@@ -207,9 +222,7 @@ struct RightWs {
         partials = V + (op == LOQT_OP_BWD_RIGHT ? bf16_bytes(T, r) : 0);
         total = partials;
         if (op == LOQT_OP_BWD_RIGHT) {
-            const int64_t tiles = ((out + 127) / 128) * ((r + 127) / 128);
-            const int64_t max_s = std::min<int64_t>(16, std::max<int64_t>(1, T / 512));
-            splits = (int)std::min(std::max<int64_t>(2, (512 + tiles / 2) / tiles), max_s);
+            splits = choose_splits(out, r, T);
             total = partials + round_up((size_t)splits * (size_t)out * (size_t)ldp * 4, 256);
         }
     }
