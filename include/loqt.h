@@ -25,12 +25,12 @@
  *   - work is enqueued on the given hipStream_t (passed as void*; NULL = the null stream)
  *     and the call returns without synchronising;
  *   - arguments are checked on the host; on error a status is returned and NOTHING is
- *     launched.  No exceptions, no hidden state, results are bit-deterministic;
+ *     launched.  No exceptions, no state kept between calls, results are bit-deterministic;
  *   - inputs must be finite;
  *   - the calls can be recorded into a HIP graph (stream capture): they allocate nothing, record
  *     no memset nodes and synchronise with nothing.  The first launch of each kernel configuration
- *     in a process sets its LDS size with hipFuncSetAttribute, so run every call once eagerly with
- *     the shapes in question before capturing it.
+ *     in a process sets its LDS size with hipFuncSetAttribute: call loqt_prepare() once before the
+ *     first capture (or run every call once eagerly with the shapes in question).
  *
  * NF4 storage (sec. 5.1: blocks of 64 weights, one scale M_beta = max |w| per block)
  *   codes  : rows x ld nibbles, two per byte.  Row i starts at byte i*ld/2; element j of
@@ -107,7 +107,7 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
  * Bytes of device workspace the given operation needs for these sizes (0 is possible).
  * The workspace must be 256-byte aligned; its contents are scratch.  Two calls that share a
  * workspace must be ordered on the same stream.  The figure covers both implementations (see
- * loqt_set_path), so it does not depend on the path option:
+ * loqt_set_path in loqt_debug.h), so it does not depend on which one runs:
  *   FWD  : U = s x B^T (T x r bf16); pre-pass paths: + bf16 copies of deq(W_q) (or the folded
  *          weight) and deq(P_q)
  *   BWD  : Z = s dy deq(P_q) (T x r bf16), fp32 slices of dB; pre-pass paths: + the same two copies
@@ -281,7 +281,7 @@ loqt_status loqt_init_compensate(const float *W, int64_t ld_w, const float *P, i
  *   loqt_merge_nq        W <- bf16( fp32(W) + s * P B ), in place, round to nearest even (Alg. 1 line 5)
  * Nothing is dequantised.  With few tokens the rank-r term is carried as a second K segment of the
  * products ([x | U] [W | P]^T and [dy | Z] [W ; B]) and no pass over the weights precedes them; from
- * T (in + out) >= out * in on (or under LOQT_PATH_FOLDED) it is folded into a transient copy of the
+ * T (in + out) >= out * in on it is folded into a transient copy of the
  * weight in the workspace, W_eff = bf16(W + s P B), as in the quantised layer, and y = x W_eff^T,
  * dx = dy W_eff are single products.
  */
@@ -383,65 +383,16 @@ loqt_status loqt_adam_step(loqt_bf16 *B, int64_t ld_B, int64_t rows, int64_t col
 loqt_status loqt_merge_schedule(double tau, double psi, int64_t cap, int n, int64_t *steps_out);
 
 /*
- * Implementation choice (process-wide; not thread-safe; default LOQT_PATH_AUTO).
- *   LOQT_PATH_FUSED  : NF4 codes are expanded inside the GEMMs' operand staging (global memory
- *                      -> registers -> LDS), no extra pass over the weights.
- *   LOQT_PATH_PREPASS: NF4 operands are expanded to bf16 in the workspace by one streaming pass
- *                      per call (transposed where the product needs it), then every product is
- *                      a K-contiguous bf16 GEMM fed by direct global->LDS loads.
- *   LOQT_PATH_FOLDED : as PREPASS, but forward and backward first fold the rank-r term into the
- *                      bf16 copy of the weight, W_eff = deq(W_q) + s deq(P_q) B (a rank-r product of
- *                      2 out in r flop with fp32 accumulation), and then run single products
- *                      y = x W_eff^T and dx = dy W_eff.  The intermediate U is not formed; Z still is
- *                      (dB = Z^T x).  Cheaper than carrying the rank-r term through every token
- *                      (2 T r (in + out) flop per pass) from T = out in / (in + out) tokens up.
- *   LOQT_PATH_AUTO   : forward and backward always take the pre-pass family (measured ahead of the
- *                      fused form at every token count from 16 up), folded when T (in + out) >= out in --
- *                      except that the backward pass, which has Z = s dy deq(P_q) at hand anyway, keeps the
- *                      rank-r term as a second K segment of the dx product when out > 0.73 T (2 T r in flop at
- *                      the rate of the large products instead of 2 out in r at the rate of the fold);
- *                      the merge is fused below 1024 columns (`in`), pre-pass above.
- * All compute the same quantities; results differ only in rounding order, within the stated
- * tolerance.
+ * loqt_prepare -- optional set-up for callers that record their first call into a HIP graph (or want the first
+ * call of a serving loop to cost what the others do).  Every GEMM kernel of the library needs its LDS size raised
+ * above the default once per process; without this call that happens at the first launch of each kernel
+ * configuration, which is not allowed while a stream is being captured.  loqt_prepare does it for all of them on
+ * the calling thread's current device and looks up the device address of the fixed scratch of
+ * loqt_absmax_dq_compress_static.  It launches nothing and allocates nothing; it may be called more than once.
+ * (The calls above keep no other state: implementation and tile choices are functions of the sizes.  The
+ * test / tuning overrides of those choices and the per-kernel timers are declared in loqt_debug.h.)
  */
-enum { LOQT_PATH_AUTO = 0, LOQT_PATH_FUSED = 1, LOQT_PATH_PREPASS = 2, LOQT_PATH_FOLDED = 3 };
-loqt_status loqt_set_path(int path);
-/* The implementation (FUSED, PREPASS or FOLDED) the current option selects for these sizes. */
-int loqt_resolved_path(int op, int64_t T, int64_t out, int64_t in);
-
-/*
- * Tile-shape option (process-wide, not thread-safe; for tests and tuning).  The products of the
- * pre-pass family (every product of the layer calls of sec. 2.2 / 2.4 and the merge of Alg. 1 line 5
- * when it takes that path) run on work-group tiles of 256x256, 256x128 or 128x128 outputs, chosen from
- * the sizes.  LOQT_TILE_AUTO keeps that choice; the other values force one shape for every such product
- * whatever its size (the compensation step of Alg. 2 and the dense merge always use 128x128).  All
- * shapes compute the same quantities; results differ only in summation order.  Returns
- * LOQT_INVALID_ARG for any other value.
- */
-enum { LOQT_TILE_AUTO = 0, LOQT_TILE_256x256 = 1, LOQT_TILE_256x128 = 2, LOQT_TILE_128x128 = 3 };
-loqt_status loqt_set_tile(int tile);
-/*
- * Diagnostic (host only, no GPU work): how a bf16-output product of M rows and N columns (plus Nx extra
- * columns that share the left operand, 0 if none) that is large enough for 256x256 tiles is laid out
- * under LOQT_TILE_AUTO.  *n_large = 0: one launch of 256x256 tiles; otherwise the first *n_large columns
- * (a multiple of 256, < N) go out as 256x256 tiles in whole rounds of 256 and the remaining columns, with
- * the extra ones, as a second launch of 128x128 tiles.  *rounds = the estimated duration in rounds of
- * 256x256 tiles.  Either pointer may be NULL.  Returns LOQT_BAD_SHAPE for M, N <= 0 or Nx < 0.
- */
-loqt_status loqt_plan_product(int64_t M, int64_t N, int64_t Nx, int64_t *n_large, double *rounds);
-
-/*
- * Optional per-kernel timing (diagnostics for benchmarks; off by default).
- * While enabled, every kernel launch of the library is bracketed by HIP events recorded on
- * the launch stream.  loqt_timing_read synchronises with the recorded events and returns,
- * for kernel slot `slot` (0 <= slot < loqt_timing_slots()), its name, launch count and summed
- * device time in milliseconds since the last loqt_timing_enable(1).  Not thread-safe; at most
- * LOQT_TIMING_MAX_EVENTS launches are recorded per enable, later ones are not timed.
- */
-#define LOQT_TIMING_MAX_EVENTS 65536
-void loqt_timing_enable(int on);
-int loqt_timing_slots(void);
-loqt_status loqt_timing_read(int slot, const char **name, int64_t *launches, double *total_ms);
+loqt_status loqt_prepare(void);
 
 #ifdef __cplusplus
 }

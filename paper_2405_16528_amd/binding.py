@@ -107,6 +107,8 @@ lib.loqt_absmax_dq_compress_static.restype = _i
 lib.loqt_absmax_dq_compress_static.argtypes = [_vp, _i64, _vp, _vp, _vp, _vp]
 lib.loqt_absmax_dq_expand.restype = _i
 lib.loqt_absmax_dq_expand.argtypes = [_vp, _vp, _vp, _i64, _vp, _vp]
+lib.loqt_prepare.restype = _i
+lib.loqt_prepare.argtypes = []
 lib.loqt_set_path.restype = _i
 lib.loqt_set_path.argtypes = [_i]
 lib.loqt_plan_product.restype = _i
@@ -394,6 +396,11 @@ def loqt_init_compensate(W: torch.Tensor, P: torch.Tensor, s: float, iters: int,
                                     1 if warm_start else 0, out.codes.data_ptr(), out.absmax.data_ptr(), out.ld,
                                     B.data_ptr(), _pitch(B), *_ws_args(ws), _stream()), "loqt_init_compensate")
     return out
+
+
+def loqt_prepare() -> None:
+    """Raise the LDS size of every kernel once (needed before a first call is recorded into a HIP graph)."""
+    _check(lib.loqt_prepare(), "loqt_prepare")
 
 
 def set_path(path: int) -> None:

@@ -1255,6 +1255,14 @@ loqt_status loqt_absmax_dq_expand(const uint8_t* codes8, const float* c1, const 
     return LOQT_OK;
 }
 
+loqt_status loqt_prepare(void) {
+    LOQT_HIP(prepare_nt_kernels());
+    LOQT_HIP(prepare_fused_kernels());
+    void* scratch_ptr = nullptr;
+    LOQT_HIP(dq_static_scratch(&scratch_ptr));
+    return LOQT_OK;
+}
+
 loqt_status loqt_set_path(int path) {
     if (path < LOQT_PATH_AUTO || path > LOQT_PATH_FOLDED) return LOQT_INVALID_ARG;
     g_path = path;

@@ -440,17 +440,26 @@ __global__ __launch_bounds__(256) void reduce_db4_kernel(const float* __restrict
     }
 }
 
+// the kernel's LDS size has to be raised above the default once per process (first launch, or loqt_prepare)
 template <int BM, int BN, int AK, int BK0, int BK1, int EPI>
-hipError_t launch_one(const GemmParams& p, hipStream_t st) {
-    auto kern = loqt_gemm_kernel<BM, BN, AK, BK0, BK1, EPI>;
+hipError_t ensure_attr_one() {
     constexpr int smem = 2 * (BM + BN) * ROW_BYTES + 64;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(loqt_gemm_kernel<BM, BN, AK, BK0, BK1, EPI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    return hipSuccess;
+}
+
+template <int BM, int BN, int AK, int BK0, int BK1, int EPI>
+hipError_t launch_one(const GemmParams& p, hipStream_t st) {
+    auto kern = loqt_gemm_kernel<BM, BN, AK, BK0, BK1, EPI>;
+    constexpr int smem = 2 * (BM + BN) * ROW_BYTES + 64;
+    hipError_t e0 = ensure_attr_one<BM, BN, AK, BK0, BK1, EPI>();
+    if (e0 != hipSuccess) return e0;
     const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
     dim3 grid(tiles, EPI == EPI_F32_SPLITK ? p.splits : 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
@@ -464,6 +473,22 @@ bool use_big_tiles(int M, int N) {
 }
 
 }  // namespace
+
+hipError_t prepare_fused_kernels() {
+    hipError_t e;
+#define LOQT_PREP(...)                                 \
+    if ((e = ensure_attr_one<__VA_ARGS__>()) != hipSuccess) return e
+    LOQT_PREP(128, 128, KC_BF16, KC_BF16, OP_NONE, EPI_BF16);
+    LOQT_PREP(256, 256, KC_BF16, KC_NF4, KC_NF4, EPI_BF16);
+    LOQT_PREP(128, 128, KC_BF16, KC_NF4, KC_NF4, EPI_BF16);
+    LOQT_PREP(128, 128, KC_BF16, RC_NF4, OP_NONE, EPI_BF16);
+    LOQT_PREP(256, 256, KC_BF16, RC_NF4, RC_BF16, EPI_BF16);
+    LOQT_PREP(128, 128, KC_BF16, RC_NF4, RC_BF16, EPI_BF16);
+    LOQT_PREP(128, 128, RC_BF16, RC_BF16, OP_NONE, EPI_F32_SPLITK);
+    LOQT_PREP(128, 128, RC_BF16, KC_NF4, OP_NONE, EPI_MERGE);
+#undef LOQT_PREP
+    return hipSuccess;
+}
 
 int gemm_db_splits(int64_t T, int64_t r, int64_t in) {
     // enough work-groups for 256 compute units at two groups per unit, at least 512 deep

@@ -1034,17 +1034,36 @@ __global__ __launch_bounds__(256) void nt_merge_grouped_kernel(const MergeGroupP
     nt_gemm_tile<128, 128, EPI_MERGE, false, BRC>(p, xcd * per_xcd + (j - start), 0);
 }
 
+// the kernel's LDS size has to be raised above the default once per process (first launch, or loqt_prepare)
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
+hipError_t ensure_attr() {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, NtCfg<BM, BN, NS>::SMEM);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    return hipSuccess;
+}
+template <bool BRC>
+hipError_t ensure_attr_grouped() {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_merge_grouped_kernel<BRC>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, NtCfg<128, 128, 2>::SMEM);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    return hipSuccess;
+}
+
 template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
     auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS>;
     constexpr int smem = NtCfg<BM, BN, NS>::SMEM;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    hipError_t e0 = ensure_attr<BM, BN, EPI, ARC, BRC, NS>();
+    if (e0 != hipSuccess) return e0;
     const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN + (p.Nx + BN - 1) / BN);
     dim3 grid((tiles + 7) / 8 * 8, EPI == EPI_F32_SPLITK ? p.splits : 1);
     hipLaunchKernelGGL(kern, grid, dim3(256), smem, st, p);
@@ -1158,26 +1177,34 @@ hipError_t launch_merge_grouped(int slot, bool b_rc, const MergeGroupLayer* laye
     }
     constexpr int smem = NtCfg<128, 128, 2>::SMEM;
     const dim3 grid((unsigned)per_xcd_total * 8u);
-    if (b_rc) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_merge_grouped_kernel<true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(nt_merge_grouped_kernel<true>, grid, dim3(256), smem, st, g);
-    } else {
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_merge_grouped_kernel<false>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(nt_merge_grouped_kernel<false>, grid, dim3(256), smem, st, g);
-    }
+    hipError_t e0 = b_rc ? ensure_attr_grouped<true>() : ensure_attr_grouped<false>();
+    if (e0 != hipSuccess) return e0;
+    if (b_rc) hipLaunchKernelGGL(nt_merge_grouped_kernel<true>, grid, dim3(256), smem, st, g);
+    else hipLaunchKernelGGL(nt_merge_grouped_kernel<false>, grid, dim3(256), smem, st, g);
     return hipGetLastError();
+}
+
+// every kernel configuration launch_gemm_nt / launch_merge_grouped can reach
+hipError_t prepare_nt_kernels() {
+    hipError_t e;
+#define LOQT_PREP3(EPI, ARC, BRC)                                                   \
+    if ((e = ensure_attr<256, 256, EPI, ARC, BRC>()) != hipSuccess) return e;       \
+    if ((e = ensure_attr<256, 128, EPI, ARC, BRC>()) != hipSuccess) return e;       \
+    if ((e = ensure_attr<128, 128, EPI, ARC, BRC>()) != hipSuccess) return e
+    LOQT_PREP3(EPI_BF16, false, false);
+    LOQT_PREP3(EPI_MERGE, false, false);
+    LOQT_PREP3(EPI_FOLD, false, false);
+    LOQT_PREP3(EPI_BF16, false, true);
+    LOQT_PREP3(EPI_MERGE, false, true);
+    LOQT_PREP3(EPI_FOLD, false, true);
+    LOQT_PREP3(EPI_ACC_BF16, false, true);
+    LOQT_PREP3(EPI_F32_SPLITK, true, true);
+#undef LOQT_PREP3
+    if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 3>()) != hipSuccess) return e;
+    if ((e = ensure_attr<128, 128, EPI_COMP, false, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<128, 128, EPI_FOLD_F32, false, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr_grouped<true>()) != hipSuccess) return e;
+    return ensure_attr_grouped<false>();
 }
 
 // a_rc / b_rc: the operand is stored K x rows (rows contiguous) instead of rows x K

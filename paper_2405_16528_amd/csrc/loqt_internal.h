@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "../../include/loqt.h"
+#include "../../include/loqt_debug.h"
 
 namespace loqt {
 
@@ -285,6 +286,10 @@ struct DequantGroupItem {
 };
 hipError_t launch_dequantize_grouped(const DequantGroupItem* items, int n, hipStream_t st, int slot);
 hipError_t launch_merge_grouped(int slot, bool b_rc, const MergeGroupLayer* layers, int n, hipStream_t st);
+// raise the LDS size of every kernel configuration of gemm_nt.hip / gemm.hip above the default (otherwise done at the
+// first launch of each), so that a first call can be recorded into a HIP graph
+hipError_t prepare_nt_kernels();
+hipError_t prepare_fused_kernels();
 // tuning aid for benchmarks: 0 = choose by shape, 1 = 256x256, 2 = 256x128, 3 = 128x128 tiles
 extern int g_nt_tile_override;
 // how launch_gemm_nt lays out a bf16-output product (EPI_BF16) that is large enough for 256x256 tiles, and its

@@ -20,7 +20,8 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    hdr = open(os.path.join(ROOT, "include", "loqt.h")).read()
+    hdr = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                  if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(nf4_\w+|loqt_\w+)\s*\(", hdr))
     assert {"nf4_quantize", "nf4_dequantize", "loqt_linear_fwd", "loqt_linear_bwd", "loqt_merge_requant",
@@ -29,7 +30,8 @@ def test_every_declared_symbol_is_exported(lib):
             "loqt_merge_requant_right", "loqt_merge_dense", "loqt_adam_step", "loqt_merge_schedule",
             "loqt_absmax_dq_workspace_bytes", "loqt_absmax_dq_compress", "loqt_absmax_dq_expand",
             "loqt_linear_fwd_nq", "loqt_linear_bwd_nq", "loqt_merge_nq", "loqt_linear_fwd_save",
-            "loqt_linear_bwd_saved", "loqt_set_tile", "loqt_plan_product"} <= names
+            "loqt_linear_bwd_saved", "loqt_set_tile", "loqt_plan_product", "loqt_prepare",
+            "loqt_merge_batched_workspace_bytes", "loqt_absmax_dq_compress_static", "loqt_timing_enable"} <= names
     for n in names:
         assert hasattr(lib, n), f"{n} is declared in loqt.h but not exported"
 
