@@ -77,7 +77,7 @@ typedef struct loqt_nf4_mat {
 enum { LOQT_F32 = 0, LOQT_BF16 = 1 };                 /* output dtypes */
 enum { LOQT_OP_FWD = 0, LOQT_OP_BWD = 1, LOQT_OP_MERGE = 2, LOQT_OP_INIT = 3,
        LOQT_OP_FWD_RIGHT = 4, LOQT_OP_BWD_RIGHT = 5, LOQT_OP_MERGE_RIGHT = 6,
-       LOQT_OP_FWD_NQ = 7, LOQT_OP_BWD_NQ = 8 };
+       LOQT_OP_FWD_NQ = 7, LOQT_OP_BWD_NQ = 8, LOQT_OP_FWD_SAVE = 9, LOQT_OP_BWD_SAVED = 10 };
 
 /* Human-readable name of a status code (static string). */
 const char *loqt_status_string(loqt_status st);
@@ -111,6 +111,8 @@ loqt_status nf4_dequantize(const uint8_t *codes, const float *absmax, int64_t ro
  *   FWD  : U = s x B^T (T x r bf16); pre-pass paths: + bf16 copies of deq(W_q) (or the folded
  *          weight) and deq(P_q)
  *   BWD  : Z = s dy deq(P_q) (T x r bf16), fp32 slices of dB; pre-pass paths: + the same two copies
+ *   FWD_SAVE, BWD_SAVED: loqt_linear_fwd_save / loqt_linear_bwd_saved: as FWD / BWD without the copy of the
+ *          weight (it lives in the caller's w_eff) and, forward, without U
  *   MERGE: pre-pass path: bf16 deq(P_q) (T is ignored)
  *   INIT : loqt_init_compensate: bf16 copy of P, the residual W - deq(Q_c) in bf16, fp32 slices of
  *          B (T is ignored)
@@ -162,7 +164,7 @@ loqt_status loqt_linear_bwd(const loqt_bf16 *dy, int64_t ld_dy, const loqt_bf16 
  * bits).  w_eff must hold out rows of ld_weff >= in elements (ld_weff % 8 == 0, 16-byte aligned) and
  * must not be touched between the two calls; `in` tells the backward call its width.  Any number of
  * forward / backward pairs may reuse one w_eff while Wq, Pq, B and s stay the same (the micro-batches
- * of a gradient-accumulation step, sec. 3.3).  Workspace sizes are those of LOQT_OP_FWD / LOQT_OP_BWD.
+ * of a gradient-accumulation step, sec. 3.3).  Workspace sizes: LOQT_OP_FWD_SAVE / LOQT_OP_BWD_SAVED.
  */
 loqt_status loqt_linear_fwd_save(const loqt_bf16 *x, int64_t ld_x, int64_t T,
                                  const loqt_nf4_mat *Wq, const loqt_nf4_mat *Pq,
@@ -251,7 +253,11 @@ loqt_status loqt_merge_requant_right(const loqt_nf4_mat *Wq, uint8_t *codes_out,
  *     Q_c = nf4_quantize( fl32( W - s P B ) )          (B = 0 at a cold start: Q_1 = q(W))
  *     B   = P^+ ( W - deq(Q_c) ) / s                   (least squares: argmin_B |Q_c + s P B - W|_F)
  * for `iters` steps (the paper uses at most five).  Of the three forms the paper prints for the
- * B update this is the one that minimises its stated objective.  P^+ is taken as P^T: P must have
+ * B update this is the one that minimises its stated objective.  It differs from the algorithm box as
+ * printed (B <- P^+(W_hat - Q_c) with W_hat = W - P B, which for orthonormal P is this update minus the
+ * previous B) from the second iteration on: taken literally that line makes |Q + P B - W| go back up on
+ * every second iteration and end above this loop's (shown with the CPU oracle in
+ * tests/test_oracle_init.py), so it is read as the least-squares step it names.  P^+ is taken as P^T: P must have
  * orthonormal columns (Alg. 2 line 3: left singular vectors), which is a precondition, not checked.
  *   W  : fp32 out x in,  pitch ld_w (ld_w % 4 == 0, 16-byte aligned base); read only
  *   P  : fp32 out x r,   pitch ld_p (ld_p % 4 == 0, 16-byte aligned base); read only.  The caller

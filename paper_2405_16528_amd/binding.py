@@ -24,6 +24,7 @@ lib = C.CDLL(_LIB_PATH)
 F32, BF16 = 0, 1
 OP_FWD, OP_BWD, OP_MERGE, OP_INIT, OP_FWD_RIGHT, OP_BWD_RIGHT, OP_MERGE_RIGHT = 0, 1, 2, 3, 4, 5, 6
 OP_FWD_NQ, OP_BWD_NQ = 7, 8
+OP_FWD_SAVE, OP_BWD_SAVED = 9, 10
 PATH_AUTO, PATH_FUSED, PATH_PREPASS, PATH_FOLDED = 0, 1, 2, 3
 TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x128 = 0, 1, 2, 3
 STATUS_NAMES = {0: "LOQT_OK", 1: "LOQT_INVALID_ARG", 2: "LOQT_BAD_SHAPE", 3: "LOQT_MISALIGNED",

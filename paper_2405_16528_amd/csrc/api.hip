@@ -155,12 +155,14 @@ int choose_splits(int64_t M, int64_t N, int64_t K) {
     return best;
 }
 
+// `saved`: the caller keeps W_eff in a buffer of its own (loqt_linear_fwd_save / loqt_linear_bwd_saved), so the
+// workspace holds no copy of the weight (and the forward pass, always folded then, no U)
 struct FwdWs {
     size_t U, Wb, Pb, total;  // U = s x B^T; Wb = deq(W) or W_eff; Pb = deq(P)
-    FwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
+    FwdWs(int64_t T, int64_t out, int64_t in, int64_t r, bool saved = false) {
         U = 0;
-        Wb = U + bf16_bytes(T, r);
-        Pb = Wb + bf16_bytes(out, in);
+        Wb = U + (saved ? 0 : bf16_bytes(T, r));
+        Pb = Wb + (saved ? 0 : bf16_bytes(out, in));
         total = Pb + bf16_bytes(out, r);
     }
 };
@@ -168,10 +170,10 @@ struct BwdWs {
     size_t Z, Wb, Pb, partials, total;  // Z = s dy deq(P); Wb = deq(W) or W_eff; Pb = deq(P); dB slices
     int splits;
     int64_t ldp;
-    BwdWs(int64_t T, int64_t out, int64_t in, int64_t r) {
+    BwdWs(int64_t T, int64_t out, int64_t in, int64_t r, bool saved = false) {
         Z = 0;
         Wb = Z + bf16_bytes(T, r);
-        Pb = Wb + bf16_bytes(out, in);
+        Pb = Wb + (saved ? 0 : bf16_bytes(out, in));
         partials = Pb + bf16_bytes(out, r);
         ldp = (int64_t)round_up(in, 4);
         splits = choose_splits(r, in, T);
@@ -427,6 +429,8 @@ size_t loqt_workspace_bytes(int op, int64_t T, int64_t out, int64_t in, int64_t 
             const size_t pre = BwdWs(T, out, in, r).total;
             return fused > pre ? fused : pre;
         }
+        case LOQT_OP_FWD_SAVE: return T <= 0 ? 0 : FwdWs(T, out, in, r, true).total;
+        case LOQT_OP_BWD_SAVED: return T <= 0 ? 0 : BwdWs(T, out, in, r, true).total;
         case LOQT_OP_MERGE: return merge_ws_bytes(out, in, r);
         case LOQT_OP_INIT: return InitWs(out, in, r).total;
         case LOQT_OP_FWD_RIGHT:
@@ -458,7 +462,8 @@ static loqt_status fwd_impl(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
     LOQT_TRY(check_bf16(y, T, out, ld_y));
     if (!ws) return LOQT_INVALID_ARG;
     if (!aligned(ws, 256)) return LOQT_MISALIGNED;
-    if (ws_bytes < loqt_workspace_bytes(LOQT_OP_FWD, T, out, in, r)) return LOQT_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < loqt_workspace_bytes(save_weff ? LOQT_OP_FWD_SAVE : LOQT_OP_FWD, T, out, in, r))
+        return LOQT_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)hip_stream;
     const int64_t ld_u = (int64_t)round_up(r, 8);
     loqt_bf16* U = reinterpret_cast<loqt_bf16*>(ws);
@@ -466,7 +471,7 @@ static loqt_status fwd_impl(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
 
     if (save_weff) LOQT_TRY(check_bf16(save_weff, out, in, ld_save));
     if (save_weff || use_prepass(T)) {
-        const FwdWs L(T, out, in, r);
+        const FwdWs L(T, out, in, r, save_weff != nullptr);
         char* base = reinterpret_cast<char*>(ws);
         uint16_t* Wb = save_weff ? save_weff : reinterpret_cast<uint16_t*>(base + L.Wb);
         uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);
@@ -569,7 +574,8 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
     if (!aligned(dB, dB_dtype == LOQT_BF16 ? 2 : 4)) return LOQT_MISALIGNED;
     if (!ws) return LOQT_INVALID_ARG;
     if (!aligned(ws, 256)) return LOQT_MISALIGNED;
-    if (ws_bytes < loqt_workspace_bytes(LOQT_OP_BWD, T, out, in, r)) return LOQT_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < loqt_workspace_bytes(saved ? LOQT_OP_BWD_SAVED : LOQT_OP_BWD, T, out, in, r))
+        return LOQT_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)hip_stream;
     const int64_t ld_z = (int64_t)round_up(r, 8);
     loqt_bf16* Z = reinterpret_cast<loqt_bf16*>(ws);
@@ -577,7 +583,7 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
 
     GemmParams p;
     if (saved || use_prepass(T)) {
-        const BwdWs L(T, out, in, r);
+        const BwdWs L(T, out, in, r, saved != nullptr);
         char* base = reinterpret_cast<char*>(ws);
         const uint16_t* Wb = saved ? saved : reinterpret_cast<const uint16_t*>(base + L.Wb);
         uint16_t* Pb = reinterpret_cast<uint16_t*>(base + L.Pb);

@@ -63,6 +63,10 @@ def test_workspace_sizes(lib):
     assert L.loqt_workspace_bytes(L.OP_FWD_NQ, T, out, inp, r) >= T * r * 2
     assert L.loqt_workspace_bytes(L.OP_BWD_NQ, T, out, inp, r) >= T * r * 2 + 2 * r * inp * 4
     assert L.loqt_workspace_bytes(99, T, out, inp, r) == 0
+    # the saved pair keeps the weight in the caller's buffer: no out x in copy in the workspace
+    assert L.loqt_workspace_bytes(L.OP_FWD_SAVE, T, out, inp, r) <= fwd - out * inp * 2
+    assert L.loqt_workspace_bytes(L.OP_BWD_SAVED, T, out, inp, r) <= bwd - out * inp * 2
+    assert L.loqt_workspace_bytes(L.OP_BWD_SAVED, T, out, inp, r) >= T * r * 2 + out * r * 2 + r * inp * 4
 
 
 def test_bad_arguments_are_rejected_before_launch(lib):

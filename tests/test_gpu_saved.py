@@ -38,12 +38,17 @@ def test_saved_pair_parity(T, out, inp, r, ldw, s):
     lay, Wq, Pq, d = _setup(T, out, inp, r, seed=3 * T + out)
     y = G.bf16_empty(T, out, fill=float("nan"))
     w_eff = G.bf16_empty(out, inp, ld=ldw, fill=float("nan"))
+    # the saved calls take the smaller workspaces (no copy of the weight: it lives in w_eff)
     ws = G.workspace(L.OP_FWD, T, out, inp, r)
-    L.loqt_linear_fwd_save(d["x"], d["Wq"], d["Pq"], d["B"], s, y, w_eff, ws)
+    ws_s = G.workspace(L.OP_FWD_SAVE, T, out, inp, r)
+    assert ws_s.numel() + out * inp * 2 <= ws.numel()
+    L.loqt_linear_fwd_save(d["x"], d["Wq"], d["Pq"], d["B"], s, y, w_eff, ws_s)
     dx = G.bf16_empty(T, inp, fill=float("nan"))
     dB = torch.full((r, inp), float("nan"), dtype=torch.float32, device="cuda")
     ws2 = G.workspace(L.OP_BWD, T, out, inp, r)
-    L.loqt_linear_bwd_saved(d["dy"], d["x"], d["Pq"], s, w_eff, dx, dB, False, ws2)
+    ws2_s = G.workspace(L.OP_BWD_SAVED, T, out, inp, r)
+    assert ws2_s.numel() + out * inp * 2 <= ws2.numel()
+    L.loqt_linear_bwd_saved(d["dy"], d["x"], d["Pq"], s, w_eff, dx, dB, False, ws2_s)
     torch.cuda.synchronize()
     y_ref = O.loqt_linear_fwd(lay.x, Wq, Pq, lay.B, s)
     dx_ref, dB_ref = O.loqt_linear_bwd(lay.dy, lay.x, Wq, Pq, lay.B, s)

@@ -100,3 +100,34 @@ def test_scale_and_warm_start_consistency():
     c3, a3, B3, h3 = O.loqt_init_compensate(W, P, 1.0, 1, B0=B2)
     assert np.array_equal(c3, c1) and np.array_equal(a3, a1) and np.array_equal(B3, B1)
     assert h2 == h1[:2] and h3 == h1[2:]
+
+
+def test_the_box_line_taken_literally_does_not_descend():
+    """Alg. 2 prints the update as B <- P^+(W_hat - Q_c) with W_hat = W - P B.  For orthonormal P that is the
+    least-squares B minus the previous B: from the second iteration on it is the *increment* of the least-squares
+    solution, not the solution.  Iterated literally, the stated objective |Q_c + P B - W| is not monotone (it goes
+    back up on every second iteration) and ends well above the reading implemented (B = P^+(W - Q_c)), which is
+    non-increasing.  Both loops written out here with the oracle's quantiser."""
+    W, P = _case(128, 256, 32, seed=4)
+    Wd, Pd = W.astype(np.float64), P.astype(np.float64)
+    Pp = np.linalg.pinv(Pd)
+
+    def objective(codes, absmax, B):
+        return float(np.linalg.norm(O.nf4_dequantize_f64(codes, absmax) + Pd @ B - Wd))
+
+    # the line as printed
+    B = np.zeros((32, 256))
+    W_hat = Wd.copy()
+    literal = []
+    for _ in range(5):
+        codes, absmax = O.nf4_quantize(W_hat.astype(np.float32))
+        B = Pp @ (W_hat - O.nf4_dequantize_f64(codes, absmax))
+        W_hat = Wd - Pd @ B
+        literal.append(objective(codes, absmax, B))
+    # the least-squares reading (s = 1): the oracle's loop
+    _, _, _, hist = O.loqt_init_compensate(W, P, 1.0, 5)
+    assert all(b <= a * (1 + 1e-12) for a, b in zip(hist, hist[1:]))   # non-increasing
+    assert hist[-1] < 0.9 * hist[0]
+    assert literal[0] == pytest.approx(hist[0], rel=1e-9)              # the first iteration is the same (W_hat = W)
+    assert literal[1] > literal[0] and literal[3] > literal[2]         # the literal form goes back up
+    assert all(l > h * 1.05 for l, h in zip(literal[1:], hist[1:]))    # and stays above the least-squares loop
