@@ -72,7 +72,9 @@ struct NtCfg {
 
 // One output tile.  L: index of the tile in the walk order described above (tiles past the end return at once);
 // split: slice of the contraction (EPI_F32_SPLITK), else 0.
-template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
+// NOTAIL (16x16x32 form only): every K segment is a whole number of k-tiles, so no tile ever takes the register path
+// and the loads need no mask -- see hot_load_live.
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2, bool NOTAIL = false>
 __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, const int split) {
     using Cfg = NtCfg<BM, BN, NS>;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, STAGE = Cfg::STAGE;
@@ -384,6 +386,24 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
             // tests/test_isa_guard.py checks that nothing else in the loop touches M0.  EXEC is restored to all
             // ones, the value it has in this uniform control flow.
         };
+        // The same load without the mask, for kernels whose tiles are all full (NOTAIL): two scalar instructions
+        // less per load.  A wave issues at most one instruction every four cycles, and the six-instruction form
+        // between two MFMAs of sixteen cycles each holds the second one back.  Tiles past the end of the contraction
+        // are not masked either: the tile pointers stop advancing, so such a load fetches the last tile once more
+        // into a stage nobody reads again (the loop's exit waits for them before LDS is reused).
+        auto hot_load_live = [&](int n, char* stage) {
+            const bool isA = n < Cfg::NCHA;
+            const int i = isA ? n : n - Cfg::NCHA;
+            const uint32_t o = isA ? offA[i] : offB[i];
+            const char* base = isA ? hotA : hotB;
+            const uint32_t dst = lds0 + (uint32_t)(stage - smem) + (uint32_t)((isA ? 0 : BM * ROWB) + i * 4096 + wave_s * 1024);
+            asm volatile(
+                "s_mov_b32 m0, %2\n\t"
+                "global_load_lds_dwordx4 %0, %1"
+                :
+                : "v"(o), "s"(base), "s"(dst)
+                : "memory");
+        };
         // fragment u (A fragments first) of k16 step ks of the tile at `stage` into buffer nb
         auto read_unit = [&](int ks, int nb, int u, const char* stage) {
             const int coff = ((2 * ks) ^ fsw) << 4;
@@ -490,7 +510,11 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
 #pragma unroll
                     for (int u = t * RPS; u < (t + 1) * RPS && u < NU2; ++u) rd16(RKS, CB ^ 1, u, rstage);
                 }
-                if constexpr (LD >= 10) {
+                if constexpr (LD >= 100) {
+                    // spread form without masks (schedule slot LD - 100 + t)
+                    const int g = LD - 100 + t;
+                    if (g % 3 == 0 && g / 3 < Cfg::NCH) hot_load_live(g / 3, lstage);
+                } else if constexpr (LD >= 10) {
                     // spread form: the whole tile, one load every third slot from slot LD - 10 of the schedule on
                     // (this range starts at schedule slot LD - 10)
                     constexpr int LSPREAD = 3;
@@ -577,6 +601,21 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
 #pragma unroll
                 for (int u = 0; u < NU2; ++u) rd16(0, 0, u, smem);
             }
+            if constexpr (NOTAIL) {
+                for (int kt = kt_begin; kt < kt_end; ++kt) {
+                    char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
+                    char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
+                    slots16(I0{}, I0{}, SH{}, I2{}, I1{}, NOLD{}, cur, cur, 0);
+                    __syncthreads();  // X
+                    if (kt + 2 < kt_end) hot_advance(kt + 2);
+                    slots16(I0{}, SH{}, SE{}, I0{}, I0{}, std::integral_constant<int, 100>{}, cur, cur, 0);
+                    slots16(I1{}, I0{}, SH{}, I0{}, I0{}, std::integral_constant<int, 100 + NS2 / 2>{}, cur, cur, 0);
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS2 - 1) / 3 + 1) : "memory");
+                    __syncthreads();  // Y
+                    slots16(I1{}, SH{}, SE{}, I1{}, I0{}, std::integral_constant<int, 100 + NS2>{}, nxt, cur, 0);
+                }
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the loads past the end, before LDS is reused
+            } else
             for (int kt = kt_begin; kt < kt_end; ++kt) {
                 char* cur = smem + ((kt - kt_begin) & 1) * STAGE;
                 char* nxt = smem + (((kt - kt_begin) & 1) ^ 1) * STAGE;
@@ -980,10 +1019,10 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
 }
 
 // Work-groups are dealt to the 8 XCDs round-robin by the hardware; each XCD walks a contiguous range of tiles.
-template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2, bool NOTAIL = false>
 __global__ __launch_bounds__(256) void nt_gemm_kernel(const GemmParams p) {
     const int per_xcd = gridDim.x >> 3;
-    nt_gemm_tile<BM, BN, EPI, ARC, BRC, NS>(p, (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), blockIdx.y);
+    nt_gemm_tile<BM, BN, EPI, ARC, BRC, NS, NOTAIL>(p, (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3), blockIdx.y);
 }
 
 // The merges of several layers (Alg. 1 line 5, one layer after the other) as ONE launch: the tiles of all layers
@@ -1035,11 +1074,11 @@ __global__ __launch_bounds__(256) void nt_merge_grouped_kernel(const MergeGroupP
 }
 
 // the kernel's LDS size has to be raised above the default once per process (first launch, or loqt_prepare)
-template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2, bool NOTAIL = false>
 hipError_t ensure_attr() {
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS, NOTAIL>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, NtCfg<BM, BN, NS>::SMEM);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -1058,11 +1097,15 @@ hipError_t ensure_attr_grouped() {
     return hipSuccess;
 }
 
-template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2>
+template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2, bool NOTAIL = false>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS>;
+    if constexpr (EPI == EPI_BF16 && BM == 256 && BN == 256 && NS == 2 && !NOTAIL) {
+        // the plain bf16 products on 256x256 tiles have a variant for contractions that are whole k-tiles
+        if (p.A[0].K % BK == 0 && p.A[1].K % BK == 0) return launch_nt<BM, BN, EPI, ARC, BRC, NS, true>(p, st);
+    }
+    auto kern = nt_gemm_kernel<BM, BN, EPI, ARC, BRC, NS, NOTAIL>;
     constexpr int smem = NtCfg<BM, BN, NS>::SMEM;
-    hipError_t e0 = ensure_attr<BM, BN, EPI, ARC, BRC, NS>();
+    hipError_t e0 = ensure_attr<BM, BN, EPI, ARC, BRC, NS, NOTAIL>();
     if (e0 != hipSuccess) return e0;
     const int tiles = ((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN + (p.Nx + BN - 1) / BN);
     dim3 grid((tiles + 7) / 8 * 8, EPI == EPI_F32_SPLITK ? p.splits : 1);
@@ -1201,6 +1244,8 @@ hipError_t prepare_nt_kernels() {
     LOQT_PREP3(EPI_F32_SPLITK, true, true);
 #undef LOQT_PREP3
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 3>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 256, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 256, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_COMP, false, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_FOLD_F32, false, true>()) != hipSuccess) return e;
     if ((e = ensure_attr_grouped<true>()) != hipSuccess) return e;
