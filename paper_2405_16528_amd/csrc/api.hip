@@ -598,8 +598,12 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
             const int64_t tm = (T + 255) / 256, tm128 = (T + 127) / 128;
             const int64_t t_dx = tm * ((in + 255) / 256), t_z = tm * ((r + 255) / 256);
             // Z alone: 256x256 tiles when they fill the chip, else 128x128 in rounds of 512
+            // (with a long contraction and 224 .. 256 tiles of 256x128 it runs on those: about 0.55 of a round)
+            const int64_t t_z2 = tm * ((r + 127) / 128);
             const double z_alone = t_z >= 224 ? plan_bf16_product(T, r, 0).cost
-                                              : 0.68 * (double)((tm128 * ((r + 127) / 128) + 511) / 512);
+                                   : (out >= 2048 && t_z2 >= 224 && t_z2 <= 256)
+                                       ? 0.55
+                                       : 0.68 * (double)((tm128 * ((r + 127) / 128) + 511) / 512);
             z_with_dx = t_dx >= 224 && plan_bf16_product(T, in, r).cost < plan_bf16_product(T, in, 0).cost + z_alone;
         }
         if (!z_with_dx) {

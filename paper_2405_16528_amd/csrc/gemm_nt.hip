@@ -125,7 +125,7 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
     // written per instruction, which on this power-limited part is worth a few per cent of clock (measured: 5 %
     // with both operands K-contiguous, 1 % with B stored K x rows; on 128x128 tiles nothing, or a loss).  Their accumulators:
     // 16x16 tiles (ti, tj) of the wave tile, lane = row ti*16 + (lane & 15), register r = column tj*16 + 4*(lane >> 4) + r.
-    constexpr bool MF16 = EPI == EPI_BF16 && BM == 256 && BN == 256;
+    constexpr bool MF16 = EPI == EPI_BF16 && BM == 256 && (BN == 256 || BN == 128) && NS == 2;
     constexpr int TM2 = MF16 ? 2 * TM : 1, TN2 = MF16 ? 2 * TN : 1;
     f32x4 acc16[TM2][TN2];
 #pragma unroll
@@ -443,6 +443,10 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
         // ones.  Step B: the MFMAs of step 1; the barrier sits in its middle, and after it come the reads of the next
         // tile's step 0 and the first half of tile kt+2.
         constexpr int NM2 = TM2 * TN2, NS2 = NM2 / 2, NU2 = TM2 + TN2;
+        // the loads of a tile go out one every LSP-th slot over the last three quarters of the previous tile's slots
+        // (256x256: 16 loads over 48 slots; 256x128: 12 over 24); LBY of them precede barrier Y
+        constexpr int LSP = MF16 ? (3 * NS2 / 2) / Cfg::NCH : 1, LBY = MF16 ? (NS2 + LSP - 1) / LSP : 0;
+        constexpr int RPQ = MF16 ? (NU2 + NS2 / 2 - 1) / (NS2 / 2) : 1;  // fragment reads per slot over a quarter of the slots
         const int frow16 = lane & 15, q4 = lane >> 4;
         uint32_t a_ko[2], b_ko[2];  // K-contiguous tiles: byte offset of this lane's fragment row and chunk per k32 step
         int a_rc16[ARC ? TM2 : 1], b_rc16[BRC ? TN2 : 1];
@@ -513,13 +517,12 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                 if constexpr (LD >= 100) {
                     // spread form without masks (schedule slot LD - 100 + t)
                     const int g = LD - 100 + t;
-                    if (g % 3 == 0 && g / 3 < Cfg::NCH) hot_load_live(g / 3, lstage);
+                    if (g % LSP == 0 && g / LSP < Cfg::NCH) hot_load_live(g / LSP, lstage);
                 } else if constexpr (LD >= 10) {
                     // spread form: the whole tile, one load every third slot from slot LD - 10 of the schedule on
                     // (this range starts at schedule slot LD - 10)
-                    constexpr int LSPREAD = 3;
                     const int g = LD - 10 + t;
-                    if (g % LSPREAD == 0 && g / LSPREAD < Cfg::NCH) hot_load(I2tag{}, g / LSPREAD, lstage, live);
+                    if (g % LSP == 0 && g / LSP < Cfg::NCH) hot_load(I2tag{}, g / LSP, lstage, live);
                 } else if constexpr (LD >= 0) {
                     const int tl = t - (NSL - LST * LSL);
                     if (tl >= 0 && tl % LST == 0) {
@@ -610,9 +613,9 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                     if (kt + 2 < kt_end) hot_advance(kt + 2);
                     slots16(I0{}, SH{}, SE{}, I0{}, I0{}, std::integral_constant<int, 100>{}, cur, cur, 0);
                     slots16(I1{}, I0{}, SH{}, I0{}, I0{}, std::integral_constant<int, 100 + NS2 / 2>{}, cur, cur, 0);
-                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS2 - 1) / 3 + 1) : "memory");
+                    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LBY) : "memory");
                     __syncthreads();  // Y
-                    slots16(I1{}, SH{}, SE{}, I1{}, I0{}, std::integral_constant<int, 100 + NS2>{}, nxt, cur, 0);
+                    slots16(I1{}, SH{}, SE{}, std::integral_constant<int, RPQ>{}, I0{}, std::integral_constant<int, 100 + NS2>{}, nxt, cur, 0);
                 }
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the loads past the end, before LDS is reused
             } else
@@ -634,11 +637,11 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
                 // tile kt+1 must have landed; the loads of tile kt+2 issued so far (schedule slots 0-31: 11 of them)
                 // came after it and may stay in flight, provided they went out as direct loads (a masked load may
                 // not count)
-                if (live2 != 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS2 - 1) / 3 + 1) : "memory");
+                if (live2 != 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LBY) : "memory");
                 else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();  // Y
                 // harmless stale reads after the last tile
-                slots16(I1{}, SH{}, SE{}, I1{}, I0{}, std::integral_constant<int, 10 + NS2>{}, nxt, cur, live2);
+                slots16(I1{}, SH{}, SE{}, std::integral_constant<int, RPQ>{}, I0{}, std::integral_constant<int, 10 + NS2>{}, nxt, cur, live2);
             }
         } else {
         if (kt_begin < kt_end) {
@@ -1099,7 +1102,7 @@ hipError_t ensure_attr_grouped() {
 
 template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2, bool NOTAIL = false>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    if constexpr (EPI == EPI_BF16 && BM == 256 && BN == 256 && NS == 2 && !NOTAIL) {
+    if constexpr (EPI == EPI_BF16 && BM == 256 && (BN == 256 || BN == 128) && NS == 2 && !NOTAIL) {
         // the plain bf16 products on 256x256 tiles have a variant for contractions that are whole k-tiles
         if (p.A[0].K % BK == 0 && p.A[1].K % BK == 0) return launch_nt<BM, BN, EPI, ARC, BRC, NS, true>(p, st);
     }
@@ -1158,6 +1161,10 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
         const int K = p.A[0].K + p.A[1].K;
         const bool light = (EPI == EPI_BF16 && K >= 2048) || EPI == EPI_FOLD || EPI == EPI_ACC_BF16;
         choice = (light && tiles(256, 256) >= 224) ? 1 : 3;
+        // skinny bf16 products with a long contraction (Z = s dy deq(P) at rank 1024: 8192 x 1024 outputs) fill the
+        // chip with 256x128 tiles, one per compute unit, at half the LDS traffic per flop of the 128x128 ones
+        if (EPI == EPI_BF16 && choice == 3 && K >= 2048 && p.Nx == 0 && tiles(256, 128) >= 224 && tiles(256, 128) <= 256)
+            choice = 2;
     }
     if constexpr (EPI == EPI_BF16) {
         // 256x256 tiles run in rounds of one tile per compute unit.  When the last round would be mostly
@@ -1246,6 +1253,8 @@ hipError_t prepare_nt_kernels() {
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 3>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 256, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 256, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 128, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 128, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_COMP, false, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_FOLD_F32, false, true>()) != hipSuccess) return e;
     if ((e = ensure_attr_grouped<true>()) != hipSuccess) return e;
