@@ -125,7 +125,8 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
     // written per instruction, which on this power-limited part is worth a few per cent of clock (measured: 5 %
     // with both operands K-contiguous, 1 % with B stored K x rows; on 128x128 tiles nothing, or a loss).  Their accumulators:
     // 16x16 tiles (ti, tj) of the wave tile, lane = row ti*16 + (lane & 15), register r = column tj*16 + 4*(lane >> 4) + r.
-    constexpr bool MF16 = EPI == EPI_BF16 && BM == 256 && (BN == 256 || BN == 128) && NS == 2;
+    constexpr bool MF16 = NS == 2 && BM == 256 &&
+                          ((EPI == EPI_BF16 && (BN == 256 || BN == 128)) || (EPI == EPI_F32_SPLITK && BN == 128));
     constexpr int TM2 = MF16 ? 2 * TM : 1, TN2 = MF16 ? 2 * TN : 1;
     f32x4 acc16[TM2][TN2];
 #pragma unroll
@@ -860,6 +861,29 @@ __device__ __forceinline__ void nt_gemm_tile(const GemmParams& p, const int L, c
             __syncthreads();
         }
         const int64_t ldb = p.w_ld >> 1, lda = p.w_ld >> 6;
+        if constexpr (MF16) {
+            // 16x16 accumulator tiles: lane holds row ti*16 + (lane & 15), columns tj*16 + 4*(lane >> 4) .. +3
+            const int frow16 = lane & 15, q4 = lane >> 4;
+#pragma unroll
+            for (int ti = 0; ti < TM2; ++ti) {
+                const int m = m0 + wm * Cfg::WTM + ti * 16 + frow16;
+#pragma unroll
+                for (int tj = 0; tj < TN2; ++tj) {
+                    const int n = n0 + wn * Cfg::WTN + tj * 16 + 4 * q4;
+                    if (m < p.M) {
+                        float* dst = C + (int64_t)m * p.ldc + n;
+                        if (n + 4 <= p.N) {
+                            *reinterpret_cast<float4*>(dst) =
+                                make_float4(p.alpha * acc16[ti][tj][0], p.alpha * acc16[ti][tj][1],
+                                            p.alpha * acc16[ti][tj][2], p.alpha * acc16[ti][tj][3]);
+                        } else {
+                            for (int j = 0; j < 4; ++j)
+                                if (n + j < p.N) dst[j] = p.alpha * acc16[ti][tj][j];
+                        }
+                    }
+                }
+            }
+        } else
 #pragma unroll
         for (int ti = 0; ti < TM; ++ti) {
             const int m = m0 + wm * Cfg::WTM + ti * 32 + frow;
@@ -1102,7 +1126,8 @@ hipError_t ensure_attr_grouped() {
 
 template <int BM, int BN, int EPI, bool ARC, bool BRC, int NS = 2, bool NOTAIL = false>
 hipError_t launch_nt(const GemmParams& p, hipStream_t st) {
-    if constexpr (EPI == EPI_BF16 && BM == 256 && (BN == 256 || BN == 128) && NS == 2 && !NOTAIL) {
+    if constexpr (((EPI == EPI_BF16 && BM == 256 && (BN == 256 || BN == 128)) ||
+                   (EPI == EPI_F32_SPLITK && BM == 256 && BN == 128)) && NS == 2 && !NOTAIL) {
         // the plain bf16 products on 256x256 tiles have a variant for contractions that are whole k-tiles
         if (p.A[0].K % BK == 0 && p.A[1].K % BK == 0) return launch_nt<BM, BN, EPI, ARC, BRC, NS, true>(p, st);
     }
@@ -1192,13 +1217,14 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     if (choice == 1) return launch_nt<256, 256, EPI, ARC, BRC>(p, st);
     if (choice == 2) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
     if constexpr (EPI == EPI_F32_SPLITK) {
-        // The fp32 slices (dB and its relatives: short rows of 128 outputs, both operands stored K x rows) wait for
-        // their loads more than for anything else on 128x128 tiles with two stages.  A 256x128 tile leaves room
-        // for a third stage (144 KB), which puts a whole k-tile more in flight: dB 0.78 -> 0.66 ms on the 7B block.
-        // (Four stages of 128x128, or three of either shape for the merge, measured slower.)
-        // From 1024 output rows (rank 1024) up; at rank 512 (1B block) it measured equal or slightly behind.
+        // The fp32 slices (dB and its relatives: short rows of 128 outputs, both operands stored K x rows) run on
+        // 256x128 tiles, one work-group per compute unit, from 1024 output rows (rank 1024) up; at rank 512 (1B block)
+        // 128x128 measured equal or slightly ahead.  History of this choice: 128x128 with two stages waited for its
+        // loads more than for anything else (dB 0.78 ms on the 7B block); 256x128 with a ring of three stages in the
+        // 32x32x16 loop 0.66 ms; the 16x16x32 loop with two stages, whose loads run up to 1.5 k-tiles ahead and are
+        // spread over the tile, 0.60 ms (A/B on one machine: 79 -> 73 us for 1024 x 4096 x 8192).
         if (g_nt_tile_override == 0 && p.M >= 1024)
-            return launch_nt<256, 128, EPI, ARC, BRC, 3>(p, st);
+            return launch_nt<256, 128, EPI, ARC, BRC, 2>(p, st);
     }
     return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
     }
@@ -1253,6 +1279,7 @@ hipError_t prepare_nt_kernels() {
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 3>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 256, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 256, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_COMP, false, true>()) != hipSuccess) return e;
