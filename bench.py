@@ -70,9 +70,9 @@ def traffic_from_profile(workload):
             mb = float(cells[4]) + float(cells[6])
         except ValueError:
             continue
-        if "<256, 256, 0, false, false, 2>" in cells[1]:
+        if "<256, 256, 0, false, false, 2, true>" in cells[1]:
             big = mb
-        elif "<128, 128, 0, false, false, 2>" in cells[1]:
+        elif "<128, 128, 0, false, false, 2, false>" in cells[1]:
             small = mb
     if big is None or small is None:
         return None
