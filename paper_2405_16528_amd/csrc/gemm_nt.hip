@@ -8,13 +8,17 @@
 // GEMM and keeps every VALU and LDS cycle of the inner loop for feeding the matrix cores.
 //
 // Work-group: 256 threads = 4 waves (2 x 2), tile BM x BN x 64; v_mfma_f32_16x16x32_bf16 for the plain bf16
-// products on 256x256 tiles (most of a training step), v_mfma_f32_32x32x16_bf16 for everything else.
+// products and the fp32 slices on 256-row tiles (most of a training step), v_mfma_f32_32x32x16_bf16 for everything
+// else (fold, merge, compensation, 128x128 tiles).
 //  * operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, no registers, no
-//    ds_write) into a ring of NS stages (two; three for the fp32 slices of dB).  There is one loop for
-//    every case: the loads of a tile are issued one by one between the MFMAs, half of them after the
-//    barrier that frees the stage and half in the next k-step, so the matrix cores never wait for a burst
-//    of loads and every load has most of a tile of MFMAs to land; loads past the end of the range are
-//    switched off through EXEC, and a k-tile that is not full (the last one of a K segment that is not a
+//    ds_write) into two stages.  The loads of a tile are issued one by one between the MFMAs, spread over
+//    the slots, never in a burst (the memory pipeline of a compute unit limits the requests in flight, and a
+//    stalled load holds back the MFMAs behind it in the in-order wave).  The 16x16x32 loop has two barriers per
+//    k-tile -- one as soon as the tile's last fragments are in registers, which frees its stage for the tile after
+//    next, one that publishes the next tile -- so a load has 1.25 to 2 k-tiles to land; the 32x32x16 loop has one
+//    barrier and issues half a tile after it and half in the next k-step.  Loads past the end of the range are
+//    switched off through EXEC (or, in the kernel variants for contractions of whole k-tiles, fetch the last tile
+//    once more into a stage nobody reads), and a k-tile that is not full (the last one of a K segment that is not a
 //    multiple of 64) is staged through registers with zero fill instead;
 //  * 16-byte chunks of an LDS row are XOR-swizzled so that fragment reads are free of bank conflicts (the
 //    pattern depends on the MFMA shape); the swizzle is applied on the global side (which chunk a lane
@@ -28,7 +32,7 @@
 //    epilogues can pack along n: bf16 results are staged through LDS and leave as whole
 //    16-byte-per-lane row segments; the fold epilogue adds the dequantised NF4 weight on the way;
 //    the merge epilogue requantises 64-blocks in registers (paper sec. 5.1, Alg. 1 line 5);
-//  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in 8-row groups so that the
+//  * tiles are dealt to the 8 XCDs in contiguous ranges and walked in groups of 4 or 8 tile rows so that the
 //    work-groups sharing an L2 also share operand panels.
 // The 256x256 kernels use every vector register; tests/test_isa_guard.py checks their generated loop.
 #include <string.h>

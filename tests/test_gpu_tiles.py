@@ -108,10 +108,10 @@ def test_forced_tiles_right_side(tile, T, out, inp, r):
 
 
 @pytest.mark.parametrize("T", [70, 200, 1100])
-def test_rank_1024_gradient_uses_the_three_stage_tiles(T):
-    """From rank 1024 up the fp32 slices of dB run on 256x128 tiles with three LDS stages, whatever the other
-    sizes: contractions (over T) of two k-tiles (fewer than the stages), of four with a short last one, and of two
-    slices with a short last k-tile."""
+def test_rank_1024_gradient_on_the_wide_tiles(T):
+    """From rank 1024 up the fp32 slices of dB run on 256x128 tiles (16x16x32 loop, masked-load variant when the
+    contraction does not end on a k-tile), whatever the other sizes: contractions (over T) of two k-tiles with a
+    short last one, of four with a short last one, and of two slices with a short last k-tile."""
     from tests import gpu_util as G
     from paper_2405_16528_amd import binding as L
     out, inp, r, s = 1100, 200, 1024, 0.5
