@@ -5,7 +5,10 @@ One "step" = one pass of the whole hot path over one batch of synthetic input fo
 transformer block: loqt_linear_fwd + loqt_linear_bwd for each of the 7 projections (nothing kept
 between the two calls), then the merge + NF4 requantisation of all 7 weights
 (loqt_merge_requant_batched).  Inputs are resident in HBM before the timed region.  Prints ONE
-JSON line (see README / DESIGN for the fields).
+JSON line: the whole-step rate (`value`), forward + backward alone (`fwd_bwd`, algorithmic and executed flops), the
+merge against its roofs (`merge`), the other mode (`other_mode`), per-kernel timings (`kernels`), the roofline of
+the dominant kernel (`roofline`, `roofline_dx`), supplementary timings (`extras`), the oracle timed on the host
+(`cpu_baseline`) and the parity of the library against it on all five workloads (`parity`).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 7b_block] [--mode plain|saved]
                     [--no-extras] [--no-cpu-baseline]
