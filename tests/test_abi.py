@@ -232,3 +232,22 @@ def test_static_entry_point_checks_before_any_gpu_call(lib):
     assert lib.loqt_absmax_dq_compress_static(P, 0, P, P, P, None) == 2
     assert lib.loqt_absmax_dq_compress_static(None, 16, P, P, P, None) == 1
     assert lib.loqt_absmax_dq_compress_static(P + 2, 16, P, P, P, None) == 3
+
+
+def test_auto_rule_on_the_paper_workloads(lib):
+    """Which implementation the default picks (host-side decision, no GPU): the rank-r term is folded into the
+    transient weight from T (in + out) >= out in tokens on; the backward pass keeps it as a second K segment of the
+    dx product when the weight has more than 0.73 T rows (sec. 2.2: both are the same quantities)."""
+    from paper_2405_16528_amd import binding as L
+    r = lambda op, T, out, inp: int(lib.loqt_resolved_path(op, T, out, inp))
+    # 7B block at 8192 tokens (appendix table of model sizes): q/k/v/o and down fold in both passes, gate / up only forward
+    for out, inp in [(4096, 4096), (4096, 11008)]:
+        assert r(L.OP_FWD, 8192, out, inp) == L.PATH_FOLDED and r(L.OP_BWD, 8192, out, inp) == L.PATH_FOLDED
+    assert r(L.OP_FWD, 8192, 11008, 4096) == L.PATH_FOLDED and r(L.OP_BWD, 8192, 11008, 4096) == L.PATH_PREPASS
+    # 13B block at 4096 tokens: every projection has more than 0.73 * 4096 rows
+    for out, inp in [(5120, 5120), (13824, 5120), (5120, 13824)]:
+        assert r(L.OP_FWD, 4096, out, inp) == L.PATH_FOLDED and r(L.OP_BWD, 4096, out, inp) == L.PATH_PREPASS
+    # few tokens: carrying the rank-r term through the tokens is cheaper than folding it
+    assert r(L.OP_FWD, 256, 4096, 4096) == L.PATH_PREPASS and r(L.OP_BWD, 256, 4096, 4096) == L.PATH_PREPASS
+    # the boundary T (in + out) = out in
+    assert r(L.OP_FWD, 2048, 4096, 4096) == L.PATH_FOLDED and r(L.OP_FWD, 2047, 4096, 4096) == L.PATH_PREPASS
