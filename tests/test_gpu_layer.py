@@ -224,3 +224,32 @@ def test_merge_batched_matches_single():
     torch.cuda.synchronize()
     for (_, dst, _, _, _), ref in zip(layers, singles):
         assert torch.equal(dst.codes, ref.codes) and torch.equal(dst.absmax, ref.absmax)
+
+
+def test_merge_batched_grouped_launches_mixed_list():
+    """The batched merge runs the wide weights (1024 columns and more) of a list as grouped launches of at most 24
+    weights and the narrow ones one by one.  A list of 27 weights of mixed shapes -- ragged rows and columns, column
+    counts that are not multiples of 64, narrow weights in between, in place and into separate outputs -- must give
+    the bits of 27 single calls (Alg. 1 line 5 per layer; the grouping is only a launch layout)."""
+    from tests import gpu_util as G
+    from paper_2405_16528_amd import binding as L
+    shapes = [(300, 1088, 64), (130, 1500, 128), (512, 192, 64), (260, 1024, 32), (64, 2112, 96), (200, 1030, 40)]
+    base = [_setup(8, out, inp, r, seed=70 + i) for i, (out, inp, r) in enumerate(shapes)]
+    layers, singles = [], []
+    for k in range(27):
+        i = k % len(shapes)
+        out, inp, r = shapes[i]
+        lay, Wq, Pq, d = base[i]
+        s = 0.25 + 0.125 * (k % 3)
+        src = L.NF4Tensor(d["Wq"].codes.clone(), d["Wq"].absmax.clone(), out, inp, d["Wq"].ld)
+        singles.append(L.loqt_merge_requant(src, d["Pq"], d["B"], s, out=L.NF4Tensor.empty(out, inp)))
+        in_place = (k % 2) == 1
+        dst = None if in_place else L.NF4Tensor.empty(out, inp)
+        layers.append((src, dst, d["Pq"], d["B"], s))
+    descs = L.make_merge_descs(layers)
+    ws = torch.empty(L.merge_descs_workspace_bytes(descs), dtype=torch.uint8, device="cuda")
+    L.loqt_merge_requant_batched(descs, ws)
+    torch.cuda.synchronize()
+    for k, ((src, dst, _, _, _), ref) in enumerate(zip(layers, singles)):
+        got = dst if dst is not None else src
+        assert torch.equal(got.codes, ref.codes) and torch.equal(got.absmax, ref.absmax), f"layer {k} {shapes[k % len(shapes)]}"
