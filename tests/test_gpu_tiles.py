@@ -18,6 +18,9 @@ SHAPES = [
     (515, 1100, 333, 192),   # odd in, K tail 13
     (70, 130, 40, 32),       # everything smaller than one tile
     (777, 264, 1000, 72),    # three row tiles, the last almost empty
+    # every contraction a whole number of k-tiles: the kernel variants whose loads carry no mask
+    (777, 1088, 1024, 128),
+    (128, 128, 64, 64),      # contractions of one and two k-tiles
 ]
 
 
