@@ -110,11 +110,12 @@ def test_forced_tiles_right_side(tile, T, out, inp, r):
     assert ey <= TOL and ex <= TOL and eb <= TOL
 
 
-@pytest.mark.parametrize("T", [70, 200, 1100])
+@pytest.mark.parametrize("T", [70, 128, 200, 1024, 1100])
 def test_rank_1024_gradient_on_the_wide_tiles(T):
     """From rank 1024 up the fp32 slices of dB run on 256x128 tiles (16x16x32 loop, masked-load variant when the
     contraction does not end on a k-tile), whatever the other sizes: contractions (over T) of two k-tiles with a
-    short last one, of four with a short last one, and of two slices with a short last k-tile."""
+    short last one, of exactly two, of four with a short last one, of sixteen whole ones, and of two slices with a
+    short last k-tile."""
     from tests import gpu_util as G
     from paper_2405_16528_amd import binding as L
     out, inp, r, s = 1100, 200, 1024, 0.5
