@@ -134,13 +134,13 @@ size_t bwd_z_bytes(int64_t T, int64_t r) { return bf16_bytes(T, r); }
 // expansions, one per NF4 operand and call.
 // Number of slices of the contraction for a product whose result is summed from fp32 slices (dB = Z^T x and its
 // relatives: M x N outputs, contraction K).  Estimated duration in k-tile steps: rounds of work-groups (256 tiles
-// of 256x128 with one work-group per compute unit from 1024 rows up, 512 tiles of 128x128 with two per unit below;
+// of 256x128 with one work-group per compute unit from 512 rows up, 512 tiles of 128x128 with two per unit below;
 // the launcher makes the same choice) times the k-tiles per slice plus a fixed prologue / epilogue, plus the slices'
 // own traffic (each is written once and read once by the reduction: M N 8 bytes against the ~12 MB the chip moves
 // in one k-tile step when the slices stay in the Infinity Cache).  A slice is at least 512 deep.
 int choose_splits(int64_t M, int64_t N, int64_t K) {
     auto cdiv = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
-    const bool wide = M >= 1024;
+    const bool wide = M >= 512;
     const int64_t tiles = wide ? cdiv(M, 256) * cdiv(N, 128) : cdiv(M, 128) * cdiv(N, 128);
     const int64_t slots = wide ? 256 : 512;
     const int64_t nkt = cdiv(K, 64);

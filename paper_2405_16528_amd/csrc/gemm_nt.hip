@@ -1222,12 +1222,12 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
     if (choice == 2) return launch_nt<256, 128, EPI, ARC, BRC>(p, st);
     if constexpr (EPI == EPI_F32_SPLITK) {
         // The fp32 slices (dB and its relatives: short rows of 128 outputs, both operands stored K x rows) run on
-        // 256x128 tiles, one work-group per compute unit, from 1024 output rows (rank 1024) up; at rank 512 (1B block)
-        // 128x128 measured equal or slightly ahead.  History of this choice: 128x128 with two stages waited for its
+        // 256x128 tiles, one work-group per compute unit, from 512 output rows (rank 512) up (1B block, rank 512:
+        // dB 0.30 -> 0.24 ms against 128x128 tiles).  History of this choice: 128x128 with two stages waited for its
         // loads more than for anything else (dB 0.78 ms on the 7B block); 256x128 with a ring of three stages in the
         // 32x32x16 loop 0.66 ms; the 16x16x32 loop with two stages, whose loads run up to 1.5 k-tiles ahead and are
         // spread over the tile, 0.60 ms (A/B on one machine: 79 -> 73 us for 1024 x 4096 x 8192).
-        if (g_nt_tile_override == 0 && p.M >= 1024)
+        if (g_nt_tile_override == 0 && p.M >= 512)
             return launch_nt<256, 128, EPI, ARC, BRC, 2>(p, st);
     }
     return launch_nt<128, 128, EPI, ARC, BRC>(p, st);
