@@ -1191,8 +1191,11 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
         const bool light = (EPI == EPI_BF16 && K >= 2048) || EPI == EPI_FOLD || EPI == EPI_ACC_BF16;
         choice = (light && tiles(256, 256) >= 224) ? 1 : 3;
         // skinny bf16 products with a long contraction (Z = s dy deq(P) at rank 1024: 8192 x 1024 outputs) fill the
-        // chip with 256x128 tiles, one per compute unit, at half the LDS traffic per flop of the 128x128 ones
-        if (EPI == EPI_BF16 && choice == 3 && K >= 2048 && p.Nx == 0 && tiles(256, 128) >= 224 && tiles(256, 128) <= 256)
+        // chip with 256x128 tiles, one per compute unit, at half the LDS traffic per flop of the 128x128 ones.  With
+        // only half as many tiles (4096 x 1024 outputs: half the compute units stay idle) they are still ahead when
+        // the contraction is very long (13B gate / up, K = 13824: 180 -> 162 us) and behind at K = 5461.
+        if (EPI == EPI_BF16 && choice == 3 && K >= 2048 && p.Nx == 0 && tiles(256, 128) <= 256 &&
+            (tiles(256, 128) >= 224 || (tiles(256, 128) >= 128 && K >= 8192)))
             choice = 2;
     }
     if constexpr (EPI == EPI_BF16) {
