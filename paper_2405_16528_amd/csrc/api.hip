@@ -155,6 +155,15 @@ int choose_splits(int64_t M, int64_t N, int64_t K) {
     return best;
 }
 
+// Z = s dy deq(P) (T x r outputs, contraction over `out`) in two fp32 slices of the contraction when its 256x128
+// tiles would fill no more than half of the compute units (1B block: 8192 x 512; 13B block: 4096 x 1024): twice
+// the work-groups at half the depth, then the fixed-order sum of the slices into bf16.  1 = one bf16 product.
+int z_splits(int64_t T, int64_t out, int64_t r) {
+    if (T < 512 || out < 2048) return 1;
+    const int64_t tiles = ((T + 255) / 256) * ((r + 127) / 128);
+    return (tiles >= 64 && tiles <= 128) ? 2 : 1;
+}
+
 // `saved`: the caller keeps W_eff in a buffer of its own (loqt_linear_fwd_save / loqt_linear_bwd_saved), so the
 // workspace holds no copy of the weight (and the forward pass, always folded then, no U)
 struct FwdWs {
@@ -167,9 +176,9 @@ struct FwdWs {
     }
 };
 struct BwdWs {
-    size_t Z, Wb, Pb, partials, total;  // Z = s dy deq(P); Wb = deq(W) or W_eff; Pb = deq(P); dB slices
-    int splits;
-    int64_t ldp;
+    size_t Z, Wb, Pb, partials, total;  // Z = s dy deq(P); Wb = deq(W) or W_eff; Pb = deq(P); fp32 slices
+    int splits, zsplits;                // slices of dB; slices of Z (1: none)
+    int64_t ldp, ldzp;
     BwdWs(int64_t T, int64_t out, int64_t in, int64_t r, bool saved = false) {
         Z = 0;
         Wb = Z + bf16_bytes(T, r);
@@ -177,7 +186,12 @@ struct BwdWs {
         partials = Pb + bf16_bytes(out, r);
         ldp = (int64_t)round_up(in, 4);
         splits = choose_splits(r, in, T);
-        total = partials + round_up((size_t)splits * (size_t)r * (size_t)ldp * 4, 256);
+        ldzp = (int64_t)round_up(r, 4);
+        zsplits = z_splits(T, out, r);
+        // the slices of Z are summed into Z before the dB product writes its own: one region serves both
+        const size_t db_bytes = (size_t)splits * (size_t)r * (size_t)ldp * 4;
+        const size_t z_bytes = zsplits > 1 ? (size_t)zsplits * (size_t)T * (size_t)ldzp * 4 : 0;
+        total = partials + round_up(db_bytes > z_bytes ? db_bytes : z_bytes, 256);
     }
 };
 struct MergeWs {
@@ -614,9 +628,17 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
             p.M = (int)T;
             p.N = (int)r;
             p.alpha = s;
-            p.C = Z;
-            p.ldc = ld_z;
-            LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, false, true, p, st));
+            if (L.zsplits > 1 && g_nt_tile_override == 0) {  // (a forced tile shape keeps the single product)
+                p.C = part;
+                p.ldc = L.ldzp;
+                p.splits = L.zsplits;
+                LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_F32_SPLITK, false, true, p, st));
+                LOQT_HIP(launch_reduce_db(part, L.zsplits, T, r, L.ldzp, Z, LOQT_BF16, ld_z, 0, st));
+            } else {
+                p.C = Z;
+                p.ldc = ld_z;
+                LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Z, EPI_BF16, false, true, p, st));
+            }
         }
         if (dx) {
             // dx = dy Wb (+ Z B when the rank-r term is not folded into Wb); Wb is out x in: K x rows

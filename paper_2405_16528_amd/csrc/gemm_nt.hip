@@ -1282,11 +1282,13 @@ hipError_t prepare_nt_kernels() {
     LOQT_PREP3(EPI_FOLD, false, true);
     LOQT_PREP3(EPI_ACC_BF16, false, true);
     LOQT_PREP3(EPI_F32_SPLITK, true, true);
+    LOQT_PREP3(EPI_F32_SPLITK, false, true);
 #undef LOQT_PREP3
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 3>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 256, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 256, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 2, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_COMP, false, true>()) != hipSuccess) return e;
@@ -1313,6 +1315,7 @@ hipError_t launch_gemm_nt(int slot, int epi, bool a_rc, bool b_rc, const GemmPar
             case EPI_COMP: return launch_nt_sized<EPI_COMP, false, true>(p, st);
             case EPI_FOLD_F32: return launch_nt_sized<EPI_FOLD_F32, false, true>(p, st);
             case EPI_ACC_BF16: return launch_nt_sized<EPI_ACC_BF16, false, true>(p, st);
+            case EPI_F32_SPLITK: return launch_nt_sized<EPI_F32_SPLITK, false, true>(p, st);
             default: break;
         }
     } else if (a_rc && b_rc) {

@@ -253,3 +253,29 @@ def test_merge_batched_grouped_launches_mixed_list():
     for k, ((src, dst, _, _, _), ref) in enumerate(zip(layers, singles)):
         got = dst if dst is not None else src
         assert torch.equal(got.codes, ref.codes) and torch.equal(got.absmax, ref.absmax), f"layer {k} {shapes[k % len(shapes)]}"
+
+
+@pytest.mark.parametrize("T,out,inp,r", [(4096, 2048, 256, 512), (4100, 2056, 264, 500)])
+def test_bwd_with_z_in_two_slices(T, out, inp, r):
+    """Z = s dy deq(P) (sec. 2.2) with T x r outputs that would fill no more than half of the compute units is
+    formed as two fp32 slices of the contraction over `out` and summed in a fixed order.  Shapes that take this
+    form (64 to 128 tiles of 256x128, out >= 2048), one of them ragged in every dimension with a contraction
+    that ends inside a k-tile; dx and dB against the oracle, and the same bits on a second call."""
+    from tests import gpu_util as G
+    from paper_2405_16528_amd import binding as L
+    s = 0.5
+    lay, Wq, Pq, d = _setup(T, out, inp, r, seed=T + r, sigma_B=2e-2)
+    res = []
+    for _ in range(2):
+        dx = G.bf16_empty(T, inp, fill=float("nan"))
+        dB = torch.full((r, inp), float("nan"), dtype=torch.float32, device="cuda")
+        L.loqt_linear_bwd(d["dy"], d["x"], d["Wq"], d["Pq"], d["B"], s, dx, dB, False,
+                          G.workspace(L.OP_BWD, T, out, inp, r))
+        torch.cuda.synchronize()
+        res.append((dx, dB))
+    dx_ref, dB_ref = O.loqt_linear_bwd(lay.dy, lay.x, Wq, Pq, lay.B, s)
+    ex = G.max_err_over_rms(O.bf16_to_f64(G.bf16_host(res[0][0])), dx_ref)
+    eb = G.max_err_over_rms(res[0][1].cpu().numpy().astype(np.float64), dB_ref)
+    print(f"two-slice Z T={T} out={out} in={inp} r={r}: err/rms dx {ex:.2e} dB {eb:.2e}")
+    assert ex <= TOL and eb <= TOL
+    assert torch.equal(res[0][0].view(torch.int16), res[1][0].view(torch.int16)) and torch.equal(res[0][1], res[1][1])
