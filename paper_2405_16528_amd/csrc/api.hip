@@ -26,7 +26,7 @@ const char* kSlotNames[SLOT_COUNT] = {"nf4_quantize", "nf4_dequantize", "gemm_u"
 }  // namespace
 
 TimedLaunch::TimedLaunch(int slot_, hipStream_t s) : stream(s), slot(slot_), idx(-1) {
-    if (!g_timing.on || g_timing.n >= LOQT_TIMING_MAX_EVENTS) return;
+    if (slot_ < 0 || !g_timing.on || g_timing.n >= LOQT_TIMING_MAX_EVENTS) return;
     idx = g_timing.n++;
     if (idx >= g_timing.created) {
         (void)hipEventCreate(&g_timing.begin[idx]);
@@ -167,12 +167,15 @@ int z_splits(int64_t T, int64_t out, int64_t r) {
 // `saved`: the caller keeps W_eff in a buffer of its own (loqt_linear_fwd_save / loqt_linear_bwd_saved), so the
 // workspace holds no copy of the weight (and the forward pass, always folded then, no U)
 struct FwdWs {
-    size_t U, Wb, Pb, total;  // U = s x B^T; Wb = deq(W) or W_eff; Pb = deq(P)
+    size_t U, Wb, Pb, split, total;  // U = s x B^T; Wb = deq(W) or W_eff; Pb = deq(P); slices of y's column remainder
+    int64_t split_floats;
     FwdWs(int64_t T, int64_t out, int64_t in, int64_t r, bool saved = false) {
         U = 0;
         Wb = U + (saved ? 0 : bf16_bytes(T, r));
         Pb = Wb + (saved ? 0 : bf16_bytes(out, in));
-        total = Pb + bf16_bytes(out, r);
+        split = Pb + bf16_bytes(out, r);
+        split_floats = remainder_split_floats(T, out);
+        total = split + round_up((size_t)split_floats * 4, 256);
     }
 };
 struct BwdWs {
@@ -191,7 +194,11 @@ struct BwdWs {
         // the slices of Z are summed into Z before the dB product writes its own: one region serves both
         const size_t db_bytes = (size_t)splits * (size_t)r * (size_t)ldp * 4;
         const size_t z_bytes = zsplits > 1 ? (size_t)zsplits * (size_t)T * (size_t)ldzp * 4 : 0;
-        total = partials + round_up(db_bytes > z_bytes ? db_bytes : z_bytes, 256);
+        // ... and so can the slices of dx's column remainder, which are summed before dB starts
+        const size_t dx_bytes = (size_t)remainder_split_floats(T, in) * 4;
+        size_t most = db_bytes > z_bytes ? db_bytes : z_bytes;
+        if (dx_bytes > most) most = dx_bytes;
+        total = partials + round_up(most, 256);
     }
 };
 struct MergeWs {
@@ -521,6 +528,8 @@ static loqt_status fwd_impl(const loqt_bf16* x, int64_t ld_x, int64_t T, const l
         p.alpha = 1.0f;
         p.C = y;
         p.ldc = ld_y;
+        p.split_ws = reinterpret_cast<float*>(base + L.split);
+        p.split_ws_floats = L.split_floats;
         LOQT_HIP(launch_gemm_nt(SLOT_GEMM_Y, EPI_BF16, false, false, p, st));
         return LOQT_OK;
     }
@@ -668,6 +677,8 @@ static loqt_status bwd_impl(const loqt_bf16* dy, int64_t ld_dy, const loqt_bf16*
                 p.Cx = Z;
                 p.ldcx = ld_z;
             }
+            p.split_ws = part;  // (the slices of Z, if any, have been summed by now; those of dB come later)
+            p.split_ws_floats = remainder_split_floats(T, in);
             LOQT_HIP(launch_gemm_nt(SLOT_GEMM_DX, EPI_BF16, false, true, p, st));
         }
         // dB = Z^T x: Z is T x r and x is T x in, both K x rows; contraction over T in slices

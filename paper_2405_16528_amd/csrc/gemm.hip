@@ -535,8 +535,9 @@ hipError_t launch_gemm(GemmId id, const GemmParams& p, hipStream_t st) {
 }
 
 hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, int64_t ldp, void* dB,
-                            int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st) {
-    TimedLaunch tl(SLOT_REDUCE_DB, st);
+                            int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st, bool timed) {
+    // (untimed when it runs inside another timed launch)
+    TimedLaunch tl(timed ? SLOT_REDUCE_DB : -1, st);
     const bool bf16 = dB_dtype == LOQT_BF16;
     if (N % 4 == 0 && ldp % 4 == 0 && ld_dB % 4 == 0 && (reinterpret_cast<uintptr_t>(partials) & 15) == 0 &&
         (reinterpret_cast<uintptr_t>(dB) & (bf16 ? 7 : 15)) == 0) {

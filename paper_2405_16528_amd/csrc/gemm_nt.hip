@@ -1168,6 +1168,19 @@ BF16Plan plan_bf16_product(int64_t M, int64_t N, int64_t Nx) {
     return plan;
 }
 
+// Scratch (floats) for the column remainder of a bf16-output product of M rows and N columns in two fp32 slices
+// of the contraction: when the plan has a remainder and its 256x128 tiles number 64 to 128 (see launch_nt_sized).
+int64_t remainder_split_floats(int64_t M, int64_t N) {
+    if (M < 512 || M * 2 > (int64_t)1 << 30) return 0;
+    if (((M + 255) / 256) * ((N + 255) / 256) < 224) return 0;  // such a product takes no 256x256 tiles at all
+    const BF16Plan plan = plan_bf16_product(M, N, 0);
+    if (plan.n1 <= 0) return 0;
+    const int64_t nb = N - plan.n1;
+    const int64_t tiles = ((M + 255) / 256) * ((nb + 127) / 128);
+    if (tiles < 64 || tiles > 128) return 0;
+    return 2 * M * ((nb + 3) / 4 * 4);
+}
+
 namespace {
 
 template <int EPI, bool ARC, bool BRC>
@@ -1218,6 +1231,22 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
             b.C = reinterpret_cast<uint16_t*>(p.C) + n1;
             hipError_t e = launch_nt<256, 256, EPI, ARC, BRC>(a, st);
             if (e != hipSuccess) return e;
+            if constexpr (!ARC) {
+                // A remainder whose 256x128 tiles would fill no more than half of the compute units (13B block at
+                // 4096 tokens: 1024 of 5120 columns, 128 tiles) goes out as two fp32 slices of the contraction,
+                // twice the work-groups at half the depth, and the fixed-order sum of the two into bf16 (75 -> 47 us)
+                const int64_t need = remainder_split_floats(p.M, p.N);
+                if (need > 0 && b.Nx == 0 && p.split_ws != nullptr && p.split_ws_floats >= need &&
+                    p.A[0].K + p.A[1].K >= 2048) {
+                    GemmParams c = b;
+                    c.C = p.split_ws;
+                    c.ldc = (b.N + 3) / 4 * 4;
+                    c.splits = 2;
+                    e = launch_nt<256, 128, EPI_F32_SPLITK, ARC, BRC, 2>(c, st);
+                    if (e != hipSuccess) return e;
+                    return launch_reduce_db(p.split_ws, 2, b.M, b.N, c.ldc, b.C, LOQT_BF16, b.ldc, 0, st, false);
+                }
+            }
             return launch_nt<128, 128, EPI, ARC, BRC>(b, st);
         }
     }
@@ -1289,6 +1318,8 @@ hipError_t prepare_nt_kernels() {
     if ((e = ensure_attr<256, 256, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, true, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, false, true, 2, true>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, false, false, 2, false>()) != hipSuccess) return e;
+    if ((e = ensure_attr<256, 128, EPI_F32_SPLITK, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_BF16, false, false, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<256, 128, EPI_BF16, false, true, 2, true>()) != hipSuccess) return e;
     if ((e = ensure_attr<128, 128, EPI_COMP, false, true>()) != hipSuccess) return e;

@@ -248,13 +248,19 @@ struct GemmParams {
     int64_t w_f32_ld;
     uint16_t* e_out;
     int64_t e_ld;
+    // EPI_BF16, optional: scratch for the fp32 slices of a column remainder that goes out in two slices of the
+    // contraction (remainder_split_floats() floats), or null
+    float* split_ws;
+    int64_t split_ws_floats;
 };
+// floats of scratch a bf16-output product of M rows and N columns can use for its column remainder (0: none)
+int64_t remainder_split_floats(int64_t M, int64_t N);
 
 // which GEMM to run
 enum GemmId { GEMM_U = 0, GEMM_Y, GEMM_Z, GEMM_DX, GEMM_DB, GEMM_MERGE };
 hipError_t launch_gemm(GemmId id, const GemmParams& p, hipStream_t st);
 hipError_t launch_reduce_db(const float* partials, int splits, int64_t M, int64_t N, int64_t ldp, void* dB,
-                            int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st);
+                            int dB_dtype, int64_t ld_dB, int accumulate, hipStream_t st, bool timed = true);
 int gemm_db_splits(int64_t T, int64_t r, int64_t in);
 
 // large-token path (gemm_nt.hip): bf16 operands stored rows x K (K contiguous) or, with the
