@@ -1247,6 +1247,13 @@ hipError_t launch_nt_sized(const GemmParams& p, hipStream_t st) {
                     return launch_reduce_db(p.split_ws, 2, b.M, b.N, c.ldc, b.C, LOQT_BF16, b.ldc, 0, st, false);
                 }
             }
+            {
+                // between 129 and 256 tiles of 256x128 (7B gate / up forward: 768 of 11008 columns; 13B gate / up
+                // forward: 1536 of 13824): that shape, one work-group per compute unit
+                const int64_t t2 = ((int64_t)(b.M + 255) / 256) * ((b.N + 127) / 128);
+                if (b.Nx == 0 && t2 > 128 && t2 <= 256 && p.A[0].K + p.A[1].K >= 2048)
+                    return launch_nt<256, 128, EPI, ARC, BRC>(b, st);
+            }
             return launch_nt<128, 128, EPI, ARC, BRC>(b, st);
         }
     }
