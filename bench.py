@@ -61,7 +61,7 @@ def traffic_from_profile(workload):
     """HBM-side bytes per gemm_y timing slot (FETCH_SIZE + WRITE_SIZE of rocprofv3 --pmc, scaled by a plain copy)
     from the committed counter summary, or None when the file does not cover the workload or the kernels it names
     no longer exist under those names.  A slot is one launch of the 256x256 kernel plus, for the gate and up
-    projections (2 of 7 launches), the 128x128 tail launch."""
+    projections (2 of 7 launches), the tail launch on 256x128 tiles."""
     if workload != "7b_block" or not os.path.exists(TRAFFIC_PROFILE):
         return None
     big = small = None
@@ -75,7 +75,7 @@ def traffic_from_profile(workload):
             continue
         if "<256, 256, 0, false, false, 2, true>" in cells[1]:
             big = mb
-        elif "<128, 128, 0, false, false, 2, false>" in cells[1]:
+        elif "<256, 128, 0, false, false, 2, true>" in cells[1]:
             small = mb
     if big is None or small is None:
         return None
@@ -588,7 +588,7 @@ def main():
 
     # dominant kernel: the 256x256 bf16-epilogue product with both operands K-contiguous, i.e. the gemm_y launches
     roofline = roof("gemm_y", "nt_gemm_kernel<256,256,EPI_BF16,false,false> (the gemm_y launches: y = x W_eff^T; for "
-                              "11008 output columns the last 768 run as a 128x128-tile launch inside the same timed slot)")
+                              "11008 output columns the last 768 run as a 256x128-tile launch inside the same timed slot)")
     if roofline is not None:
         # HBM-side bytes per launch slot (FETCH_SIZE + WRITE_SIZE, rocprofv3 --pmc, scaled by a plain copy), read from
         # the committed summary of those counter runs; not measurable from inside this process

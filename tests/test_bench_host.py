@@ -14,7 +14,7 @@ def test_traffic_comes_from_the_committed_counter_summary():
     # projection) and the summary's own rows add up to the figure
     assert t is not None and 1.5e8 < t < 5e9
     rows = [l for l in open(bench.TRAFFIC_PROFILE) if l.startswith("|") and "nt_gemm_kernel" in l.split("|")[1] and
-            ("<256, 256, 0, false, false, 2, true>" in l or "<128, 128, 0, false, false, 2, false>" in l)]
+            ("<256, 256, 0, false, false, 2, true>" in l or "<256, 128, 0, false, false, 2, true>" in l)]
     assert len(rows) == 2
     assert bench.traffic_from_profile("1b_block") is None  # not profiled: null, never a stale literal
 
